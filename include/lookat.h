@@ -1,0 +1,154 @@
+/*
+ * lookat.h -- C ABI of the MI355X (gfx950) LOOKAT library.
+ *
+ * LOOKAT stores every cached attention key as m uint8 codes (product
+ * quantisation: the head dimension d_k is cut into m subspaces of d_sub = d_k/m
+ * coordinates, each with a codebook of K = 256 centroids) and scores a query
+ * against the cache by summing m entries of a per-query lookup table instead of
+ * reconstructing keys (asymmetric distance computation).
+ *
+ * General rules for every call
+ *   - All array arguments are DEVICE pointers (HBM of the current HIP device)
+ *     unless marked "host".  The caller owns every buffer; the library neither
+ *     allocates nor frees device memory and keeps no state between calls except
+ *     a thread-local error string.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls validate their arguments on the host, enqueue kernels on `stream`
+ *     and return without waiting.  Buffers must stay valid until the stream has
+ *     run the work.
+ *   - Return value: a lookat_status.  LOOKAT_OK means "enqueued".  On any other
+ *     value nothing was enqueued and lookat_last_error() describes the reason.
+ *     The library never aborts, prints or throws.
+ *   - Arrays are dense row-major with the last index fastest, except where a
+ *     stride argument says otherwise.  Strides are in ELEMENTS of the array.
+ *   - Inputs are expected to be finite.  In the encoder a NaN distance never
+ *     compares below the running minimum (so it never wins unless it is
+ *     centroid 0's).
+ *   - Supported shapes: K == 256; d_k a multiple of 8 with 8 <= d_k <= 256;
+ *     m divides d_k, 1 <= m <= 32.  Anything else: LOOKAT_ERR_UNSUPPORTED or
+ *     LOOKAT_ERR_SHAPE.
+ */
+#ifndef LOOKAT_H
+#define LOOKAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LOOKAT_F16 = 1, /* IEEE binary16 */
+    LOOKAT_F32 = 2  /* IEEE binary32 */
+} lookat_dtype;
+
+typedef enum {
+    LOOKAT_OK = 0,
+    LOOKAT_ERR_NULL = -1,        /* a required pointer is NULL */
+    LOOKAT_ERR_SHAPE = -2,       /* non-positive size, m does not divide d_k, stride too small ... */
+    LOOKAT_ERR_DTYPE = -3,       /* dtype tag is not LOOKAT_F16 / LOOKAT_F32 */
+    LOOKAT_ERR_ALIGN = -4,       /* a pointer or stride breaks the alignment stated below */
+    LOOKAT_ERR_WORKSPACE = -5,   /* workspace missing or smaller than *_workspace_bytes() */
+    LOOKAT_ERR_UNSUPPORTED = -6, /* valid problem, but outside the shapes this build handles */
+    LOOKAT_ERR_HIP = -7          /* the HIP runtime refused a launch; text in lookat_last_error() */
+} lookat_status;
+
+/* Problem shape shared by all calls: B batch entries, H heads, head dimension
+ * d_k split into m subspaces, K centroids per subspace (must be 256, the
+ * codebook size the paper fixes in Sec. 3.4 so that a code is one byte). */
+typedef struct {
+    int32_t B, H, d_k, m, K;
+} lookat_shape;
+
+/*
+ * Key encoding (paper Sec. 3.4, "Encoding"):
+ *     codes[b,h,n,i] = argmin_c || keys[b,h,n, i*d_sub:(i+1)*d_sub] - codebooks[h,i,c,:] ||^2
+ * The squared distance is evaluated in fp64, coordinates in ascending order,
+ * with a separately rounded subtract, multiply and add per coordinate (no fused
+ * multiply-add); among equal distances the lowest index c wins.  The result is
+ * therefore unique and reproducible bit for bit.
+ *
+ *   keys       [B,H,N,d_k]  key_dtype (fp16 or fp32), 16-byte aligned, dense
+ *   codebooks  [H,m,K,d_sub] fp32, 16-byte aligned (one set per head)
+ *   codes      out; element (b,h,n,i) is written at
+ *              codes[(b*H+h)*code_stride_bh + n*m + i]; code_stride_bh >= N*m.
+ *              A caller appending to a cache [B,H,Lmax,m] at position p passes
+ *              codes = cache + p*m and code_stride_bh = Lmax*m.
+ *   N          keys per (b,h), >= 0 (N == 0 is a no-op that returns LOOKAT_OK)
+ */
+int lookat_encode_keys(const lookat_shape *shape, int64_t N,
+                       const void *keys, int key_dtype,
+                       const float *codebooks,
+                       uint8_t *codes, int64_t code_stride_bh,
+                       void *stream);
+
+/*
+ * Lookup-table construction (paper Sec. 3.5, "Precomputation Lookup Tables";
+ * Algorithm 1, first loop), for T queries per (b,h):
+ *     lut[b,h,t,i,c] = sum_j q[b,h,t, i*d_sub + j] * codebooks[h,i,c,j]
+ * accumulated in fp32.
+ *
+ *   q          [B,H,T,d_k]  q_dtype (fp16 or fp32), 16-byte aligned, dense
+ *   codebooks  [H,m,K,d_sub] fp32, 16-byte aligned
+ *   lut        out [B,H,T,m,K] fp32, 16-byte aligned
+ *   T          queries per (b,h), >= 1 (decode: T = 1)
+ */
+int lookat_build_lut(const lookat_shape *shape, int32_t T,
+                     const void *q, int q_dtype,
+                     const float *codebooks,
+                     float *lut,
+                     void *stream);
+
+/*
+ * Attention decode over the coded cache (paper Algorithm 1 after the table
+ * build: lookup-and-sum scores, softmax, weighted value sum), one query per (b,h):
+ *     s[b,h,l]   = sum_i lut[b,h,i, codes[b,h,l,i]]
+ *     out[b,h,:] = sum_l softmax_l(scale * s[b,h,:]) * values[b,h,l,:]
+ * The sequence is cut into num_splits contiguous ranges per (b,h); each range
+ * keeps a running maximum and running sum (online softmax) and the ranges are
+ * merged exactly afterwards, so the result does not depend on num_splits beyond
+ * fp32 rounding.
+ *
+ *   L               cached keys per (b,h), >= 1
+ *   lut             [B,H,m,K] fp32, 16-byte aligned
+ *   codes           element (b,h,l,i) at codes[(b*H+h)*code_stride_bh + l*m + i];
+ *                   base pointer and code_stride_bh multiples of 16 bytes
+ *   values          fp16; element (b,h,l,j) at values[(b*H+h)*value_stride_bh + l*d_k + j];
+ *                   base pointer 16-byte aligned, value_stride_bh >= L*d_k
+ *   scale           softmax scale (Algorithm 1 uses 1/sqrt(d_k))
+ *   num_splits      >= 1, or 0 to let the library choose from the shape
+ *   workspace       device scratch of at least
+ *                   lookat_attend_decode_workspace_bytes(shape, L, num_splits)
+ *                   bytes, 16-byte aligned; may be NULL when that size is 0.
+ *                   Contents before and after the call are unspecified.  Two calls
+ *                   in flight at once must not share a workspace.
+ *   out             [B,H,d_k] fp32, 16-byte aligned
+ *   scores_out      optional [B,H,L] fp32: the unscaled scores s (NULL = not stored)
+ */
+size_t lookat_attend_decode_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits);
+
+int lookat_attend_decode(const lookat_shape *shape, int64_t L,
+                         const float *lut,
+                         const uint8_t *codes, int64_t code_stride_bh,
+                         const void *values, int64_t value_stride_bh,
+                         float scale, int32_t num_splits,
+                         void *workspace, size_t workspace_bytes,
+                         float *out, float *scores_out,
+                         void *stream);
+
+/* The split count lookat_attend_decode uses when num_splits == 0 (host only,
+ * no HIP call); 0 if the shape is invalid. */
+int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);
+
+/* Host pointer to a thread-local, NUL-terminated description of the last
+ * failure on this thread; valid until the next library call on this thread. */
+const char *lookat_last_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int lookat_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOOKAT_H */

@@ -1,0 +1,24 @@
+"""MI355X-native LOOKAT: attention decode over a product-quantised key cache.
+
+The work is done by hand-written HIP kernels for gfx950 behind the C ABI declared in
+``include/lookat.h`` (``liblookat.so``).  This package is the thin Python binding:
+argument marshalling from torch tensors (device memory and streams) to that ABI.
+There is no CPU fallback: without the built library every call raises.
+"""
+from .binding import (  # noqa: F401
+    LookatError,
+    attend_decode,
+    attend_decode_auto_splits,
+    attend_decode_workspace_bytes,
+    build_lut,
+    encode_keys,
+    last_error,
+    lib_path,
+    load_library,
+    version,
+)
+
+__all__ = [
+    "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
+    "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
+]

@@ -1,0 +1,215 @@
+"""ctypes binding of liblookat.so: torch tensors in, C-ABI calls out.
+
+Marshalling only — shapes, pointers, strides, the current HIP stream.  Every step of
+the method runs in the library's kernels.  If the library is missing the calls raise
+(the product has no CPU path).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liblookat.so")
+
+LOOKAT_F16 = 1
+LOOKAT_F32 = 2
+
+_lib = None
+
+
+class LookatError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lookat status {status}: {message}")
+        self.status = status
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_k", ctypes.c_int32),
+                ("m", ctypes.c_int32), ("K", ctypes.c_int32)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built library; raises if it has not been built (python -m paper_2601_10155_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise LookatError(-100, f"{_LIB_PATH} is not built; run `python -m paper_2601_10155_amd.build`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        i32, i64, vp, sz, f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        sp = ctypes.POINTER(_Shape)
+        lib.lookat_encode_keys.argtypes = [sp, i64, vp, ctypes.c_int, vp, vp, i64, vp]
+        lib.lookat_encode_keys.restype = ctypes.c_int
+        lib.lookat_build_lut.argtypes = [sp, i32, vp, ctypes.c_int, vp, vp, vp]
+        lib.lookat_build_lut.restype = ctypes.c_int
+        lib.lookat_attend_decode_workspace_bytes.argtypes = [sp, i64, i32]
+        lib.lookat_attend_decode_workspace_bytes.restype = sz
+        lib.lookat_attend_decode_auto_splits.argtypes = [sp, i64]
+        lib.lookat_attend_decode_auto_splits.restype = i32
+        lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
+        lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_last_error.restype = ctypes.c_char_p
+        lib.lookat_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def last_error() -> str:
+    return load_library().lookat_last_error().decode()
+
+
+def version() -> int:
+    return int(load_library().lookat_version())
+
+
+def _check(status: int):
+    if status != 0:
+        raise LookatError(status, last_error())
+
+
+def _dtype_tag(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return LOOKAT_F16
+    if t.dtype == torch.float32:
+        return LOOKAT_F32
+    raise TypeError(f"expected float16 or float32 tensor, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    return t
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _bh_stride(t: torch.Tensor, name: str) -> int:
+    """Element stride between consecutive (b,h) slabs of a [B,H,L,x] tensor whose slabs are dense."""
+    B, H, L, X = t.shape
+    if t.stride(3) != 1 or (L > 1 and t.stride(2) != X):
+        raise ValueError(f"{name}: each (b,h) slab must be dense [L,{X}]")
+    sh = t.stride(1) if H > 1 else max(t.stride(0), L * X)
+    if B > 1 and t.stride(0) != H * sh:
+        raise ValueError(f"{name}: batch stride must be H times the head stride")
+    return sh
+
+
+def lookat_encode_keys(keys: torch.Tensor, codebooks: torch.Tensor, codes_out: torch.Tensor | None = None,
+                       cache: torch.Tensor | None = None, position: int = 0) -> torch.Tensor:
+    """keys [B,H,N,d_k] fp16|fp32, codebooks [H,m,256,d_sub] fp32 -> codes [B,H,N,m] uint8.
+
+    With `cache` ([B,H,Lmax,m] uint8) the codes are written in place at rows
+    position .. position+N-1 and the cache is returned."""
+    lib = load_library()
+    keys = _dev(keys, "keys").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    B, H, N, d_k = keys.shape
+    Hc, m, K, d_sub = cb.shape
+    if Hc != H or m * d_sub != d_k or cb.dtype != torch.float32:
+        raise ValueError("codebooks must be fp32 [H,m,K,d_k/m]")
+    shape = _Shape(B, H, d_k, m, K)
+    if cache is not None:
+        if cache.dtype != torch.uint8 or cache.shape[:2] != (B, H) or cache.shape[3] != m:
+            raise ValueError("cache must be uint8 [B,H,Lmax,m]")
+        if position < 0 or position + N > cache.shape[2]:
+            raise ValueError("position + N exceeds the cache length")
+        stride = _bh_stride(cache, "cache")
+        ptr = cache.data_ptr() + position * m
+        ret = cache
+    else:
+        if codes_out is None:
+            codes_out = torch.empty((B, H, N, m), dtype=torch.uint8, device=keys.device)
+        if codes_out.dtype != torch.uint8 or tuple(codes_out.shape) != (B, H, N, m) or not codes_out.is_contiguous():
+            raise ValueError("codes_out must be a contiguous uint8 [B,H,N,m] tensor")
+        stride = N * m
+        ptr = codes_out.data_ptr()
+        ret = codes_out
+    _check(lib.lookat_encode_keys(ctypes.byref(shape), N, keys.data_ptr(), _dtype_tag(keys), cb.data_ptr(),
+                                  ptr, stride, _stream(keys)))
+    return ret
+
+
+def lookat_build_lut(q: torch.Tensor, codebooks: torch.Tensor, lut_out: torch.Tensor | None = None) -> torch.Tensor:
+    """q [B,H,T,d_k] fp16|fp32 -> lut [B,H,T,m,256] fp32."""
+    lib = load_library()
+    q = _dev(q, "q").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    B, H, T, d_k = q.shape
+    Hc, m, K, d_sub = cb.shape
+    if Hc != H or m * d_sub != d_k or cb.dtype != torch.float32:
+        raise ValueError("codebooks must be fp32 [H,m,K,d_k/m]")
+    shape = _Shape(B, H, d_k, m, K)
+    if lut_out is None:
+        lut_out = torch.empty((B, H, T, m, K), dtype=torch.float32, device=q.device)
+    if lut_out.dtype != torch.float32 or lut_out.numel() != B * H * T * m * K or not lut_out.is_contiguous():
+        raise ValueError("lut_out must be a contiguous fp32 tensor of B*H*T*m*K elements")
+    _check(lib.lookat_build_lut(ctypes.byref(shape), T, q.data_ptr(), _dtype_tag(q), cb.data_ptr(),
+                                lut_out.data_ptr(), _stream(q)))
+    return lut_out
+
+
+def _decode_shape(lut, codes, values):
+    B, H, L, m = codes.shape
+    d_k = values.shape[3]
+    if lut.numel() != B * H * m * 256 or lut.dtype != torch.float32 or not lut.is_contiguous():
+        raise ValueError("lut must be contiguous fp32 [B,H,m,256]")
+    if codes.dtype != torch.uint8 or values.dtype != torch.float16:
+        raise ValueError("codes must be uint8 and values fp16")
+    if tuple(values.shape[:3]) != (B, H, L):
+        raise ValueError("values must be [B,H,L,d_k] matching codes [B,H,L,m]")
+    return _Shape(B, H, d_k, m, 256), L
+
+
+def attend_decode_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, num_splits: int = 0) -> int:
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_attend_decode_workspace_bytes(ctypes.byref(shape), L, num_splits))
+
+
+def attend_decode_auto_splits(B: int, H: int, d_k: int, m: int, L: int) -> int:
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_attend_decode_auto_splits(ctypes.byref(shape), L))
+
+
+def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,
+                         num_splits: int = 0, workspace: torch.Tensor | None = None,
+                         out: torch.Tensor | None = None, scores_out: torch.Tensor | None = None) -> torch.Tensor:
+    """lut [B,H,m,256] fp32, codes [B,H,L,m] u8, values [B,H,L,d_k] fp16 -> out [B,H,d_k] fp32.
+
+    codes / values may be views of longer caches ([B,H,Lmax,*] sliced to L rows)."""
+    lib = load_library()
+    _dev(lut, "lut"), _dev(codes, "codes"), _dev(values, "values")
+    shape, L = _decode_shape(lut, codes, values)
+    B, H, d_k = shape.B, shape.H, shape.d_k
+    cs = _bh_stride(codes, "codes")
+    vs = _bh_stride(values, "values")
+    need = int(lib.lookat_attend_decode_workspace_bytes(ctypes.byref(shape), L, num_splits))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+    if out is None:
+        out = torch.empty((B, H, d_k), dtype=torch.float32, device=values.device)
+    if out.dtype != torch.float32 or out.numel() != B * H * d_k or not out.is_contiguous():
+        raise ValueError("out must be contiguous fp32 [B,H,d_k]")
+    if scores_out is not None and (scores_out.dtype != torch.float32 or scores_out.numel() != B * H * L
+                                   or not scores_out.is_contiguous()):
+        raise ValueError("scores_out must be contiguous fp32 [B,H,L]")
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.lookat_attend_decode(ctypes.byref(shape), L, lut.data_ptr(), codes.data_ptr(), cs,
+                                    values.data_ptr(), vs, float(scale), int(num_splits), ws_ptr, ws_bytes,
+                                    out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
+                                    _stream(values)))
+    return out
+
+
+# short aliases
+encode_keys = lookat_encode_keys
+build_lut = lookat_build_lut
+attend_decode = lookat_attend_decode

@@ -1,0 +1,150 @@
+// Lookup-table construction (paper Sec. 3.5, "Precomputation Lookup Tables";
+// Algorithm 1, first loop): lut[b,h,t,i,c] = q[b,h,t]^(i) . C_{h,i}[c], fp32 accumulate.
+#include "common.h"
+
+namespace lookat {
+
+constexpr int kLutThreads = kCentroids;  // one thread per centroid
+
+template <typename QT>
+__device__ __forceinline__ float to_f32(QT v);
+template <>
+__device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float to_f32<__half>(__half v) { return __half2float(v); }
+
+// One block = one head h, one subspace i, QB consecutive queries of the flattened
+// (b, t) list.  Thread c keeps centroid c of the subspace in registers and reuses it for
+// every query of the block; the query sub-vectors sit in LDS and are read by all lanes
+// at the same address (broadcast).  Each query's 256 table entries are written as one
+// contiguous 1 KB row.
+//   grid = (ceil(B*T / QB), m, H)
+template <typename QT, int DSUB>
+__global__ __launch_bounds__(kLutThreads) void build_lut_kernel(const QT *__restrict__ q,
+                                                                const float *__restrict__ codebooks,
+                                                                float *__restrict__ lut, int B, int H, int T, int d_k,
+                                                                int m, int QB)
+{
+    extern __shared__ float q_s[];  // [QB][DSUB]
+    const int i = blockIdx.y;
+    const int h = blockIdx.z;
+    const int c = threadIdx.x;
+    const int64_t nq = (int64_t)B * T;
+    const int64_t q0 = (int64_t)blockIdx.x * QB;
+
+    for (int e = threadIdx.x; e < QB * DSUB; e += kLutThreads) {
+        const int64_t qi = q0 + e / DSUB;
+        float v = 0.f;
+        if (qi < nq) {
+            const int64_t b = qi / T, t = qi % T;
+            v = to_f32<QT>(q[((b * H + h) * T + t) * d_k + (int64_t)i * DSUB + e % DSUB]);
+        }
+        q_s[e] = v;
+    }
+
+    float row[DSUB];
+    const float *src = codebooks + (((int64_t)h * m + i) * kCentroids + c) * DSUB;
+#pragma unroll
+    for (int j = 0; j < DSUB; ++j)
+        row[j] = src[j];
+    __syncthreads();
+
+    for (int k = 0; k < QB; ++k) {
+        const int64_t qi = q0 + k;
+        if (qi >= nq)
+            break;
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < DSUB; ++j)
+            acc = fmaf(q_s[k * DSUB + j], row[j], acc);
+        const int64_t b = qi / T, t = qi % T;
+        lut[((((b * H + h) * T + t) * m) + i) * kCentroids + c] = acc;
+    }
+}
+
+// Any d_sub: centroid row streamed from memory per query.
+template <typename QT>
+__global__ __launch_bounds__(kLutThreads) void build_lut_generic_kernel(const QT *__restrict__ q,
+                                                                        const float *__restrict__ codebooks,
+                                                                        float *__restrict__ lut, int B, int H, int T,
+                                                                        int d_k, int m, int QB)
+{
+    const int d_sub = d_k / m;
+    const int i = blockIdx.y;
+    const int h = blockIdx.z;
+    const int c = threadIdx.x;
+    const int64_t nq = (int64_t)B * T;
+    const float *src = codebooks + (((int64_t)h * m + i) * kCentroids + c) * d_sub;
+    for (int k = 0; k < QB; ++k) {
+        const int64_t qi = (int64_t)blockIdx.x * QB + k;
+        if (qi >= nq)
+            break;
+        const int64_t b = qi / T, t = qi % T;
+        const QT *qv = q + ((b * H + h) * T + t) * d_k + (int64_t)i * d_sub;
+        float acc = 0.f;
+        for (int j = 0; j < d_sub; ++j)
+            acc = fmaf(to_f32<QT>(qv[j]), src[j], acc);
+        lut[((((b * H + h) * T + t) * m) + i) * kCentroids + c] = acc;
+    }
+}
+
+template <typename QT>
+static void launch_build_lut(const lookat_shape *s, int T, const void *q, const float *codebooks, float *lut,
+                             hipStream_t st)
+{
+    const int d_sub = s->d_k / s->m;
+    const int64_t nq = (int64_t)s->B * T;
+    // queries per block: reuse the centroid registers, but keep >= ~1024 blocks in flight
+    int QB = 1;
+    while (QB < 16 && (nq / (QB * 2)) * s->m * s->H >= 1024)
+        QB *= 2;
+    dim3 grid((unsigned)((nq + QB - 1) / QB), (unsigned)s->m, (unsigned)s->H);
+    dim3 block(kLutThreads);
+    const QT *qp = static_cast<const QT *>(q);
+#define LOOKAT_LUT_CASE(D)                                                                                         \
+    case D:                                                                                                        \
+        hipLaunchKernelGGL((build_lut_kernel<QT, D>), grid, block, (size_t)QB * D * sizeof(float), st, qp,         \
+                           codebooks, lut, s->B, s->H, T, s->d_k, s->m, QB);                                       \
+        break;
+    switch (d_sub) {
+        LOOKAT_LUT_CASE(1)
+        LOOKAT_LUT_CASE(2)
+        LOOKAT_LUT_CASE(4)
+        LOOKAT_LUT_CASE(8)
+        LOOKAT_LUT_CASE(16)
+        LOOKAT_LUT_CASE(32)
+        LOOKAT_LUT_CASE(64)
+    default:
+        hipLaunchKernelGGL((build_lut_generic_kernel<QT>), grid, block, 0, st, qp, codebooks, lut, s->B, s->H, T,
+                           s->d_k, s->m, QB);
+        break;
+    }
+#undef LOOKAT_LUT_CASE
+}
+
+}  // namespace lookat
+
+extern "C" int lookat_build_lut(const lookat_shape *shape, int32_t T, const void *q, int q_dtype,
+                                const float *codebooks, float *lut, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (T <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "T=%d must be positive", T);
+    if (q_dtype != LOOKAT_F16 && q_dtype != LOOKAT_F32)
+        return fail(LOOKAT_ERR_DTYPE, "q_dtype=%d is neither LOOKAT_F16 nor LOOKAT_F32", q_dtype);
+    if (!q || !codebooks || !lut)
+        return fail(LOOKAT_ERR_NULL, "q, codebooks and lut must be non-NULL");
+    if (!aligned16(q) || !aligned16(codebooks) || !aligned16(lut))
+        return fail(LOOKAT_ERR_ALIGN, "q, codebooks and lut must be 16-byte aligned");
+    if ((int64_t)shape->B * T > 0x7fffffffLL || shape->H > 65535)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "B*T or H too large for one launch");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (q_dtype == LOOKAT_F16)
+        launch_build_lut<__half>(shape, T, q, codebooks, lut, st);
+    else
+        launch_build_lut<float>(shape, T, q, codebooks, lut, st);
+    return check_launch("lookat_build_lut");
+}

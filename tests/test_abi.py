@@ -1,0 +1,103 @@
+"""The C-ABI library: it loads, exports every symbol include/lookat.h declares, and turns
+bad arguments into status codes before touching the GPU.  CPU only (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lookat.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2601_10155_amd import binding
+    if not os.path.exists(binding.lib_path()):
+        from paper_2601_10155_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lookat_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
+
+
+def test_version_and_error_string(lib):
+    assert lib.lookat_version() >= 100
+    assert isinstance(lib.lookat_last_error(), bytes)
+
+
+from paper_2601_10155_amd.binding import _Shape as Shape  # noqa: E402  (the struct lookat_shape)
+
+
+OK, E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WS, E_UNSUP = 0, -1, -2, -3, -4, -5, -6
+FAKE = 0x10000  # 16-byte aligned, never dereferenced: validation fails first
+
+
+def test_encode_argument_errors(lib):
+    s = Shape(1, 1, 64, 4, 256)
+    f = lib.lookat_encode_keys
+    assert f(None, 1, FAKE, 2, FAKE, FAKE, 4, None) == E_NULL
+    assert f(ctypes.byref(s), 0, None, 2, None, None, 0, None) == OK          # N = 0: no-op
+    assert f(ctypes.byref(s), -1, FAKE, 2, FAKE, FAKE, 4, None) == E_SHAPE
+    assert f(ctypes.byref(s), 1, FAKE, 7, FAKE, FAKE, 4, None) == E_DTYPE
+    assert f(ctypes.byref(s), 1, None, 2, FAKE, FAKE, 4, None) == E_NULL
+    assert f(ctypes.byref(s), 2, FAKE, 2, FAKE, FAKE, 4, None) == E_SHAPE      # stride < N*m
+    assert f(ctypes.byref(s), 1, FAKE + 4, 2, FAKE, FAKE, 4, None) == E_ALIGN
+    assert b"aligned" in lib.lookat_last_error()
+    for bad, code in ((Shape(1, 1, 64, 5, 256), E_SHAPE), (Shape(1, 1, 64, 4, 128), E_SHAPE),
+                      (Shape(0, 1, 64, 4, 256), E_SHAPE), (Shape(1, 1, 60, 4, 256), E_UNSUP),
+                      (Shape(1, 1, 512, 4, 256), E_UNSUP), (Shape(1, 1, 256, 64, 256), E_UNSUP)):
+        assert f(ctypes.byref(bad), 1, FAKE, 2, FAKE, FAKE, 64, None) == code
+
+
+def test_build_lut_argument_errors(lib):
+    s = Shape(2, 3, 64, 4, 256)
+    f = lib.lookat_build_lut
+    assert f(ctypes.byref(s), 0, FAKE, 1, FAKE, FAKE, None) == E_SHAPE
+    assert f(ctypes.byref(s), 1, FAKE, 0, FAKE, FAKE, None) == E_DTYPE
+    assert f(ctypes.byref(s), 1, FAKE, 1, None, FAKE, None) == E_NULL
+    assert f(ctypes.byref(s), 1, FAKE, 1, FAKE, FAKE + 8, None) == E_ALIGN
+
+
+def test_attend_decode_argument_errors(lib):
+    s = Shape(2, 3, 64, 4, 256)
+    f = lib.lookat_attend_decode
+    ws = lib.lookat_attend_decode_workspace_bytes
+    L = 1000
+    args = lambda **kw: [kw.get("shape", ctypes.byref(s)), kw.get("L", L), kw.get("lut", FAKE), kw.get("codes", FAKE),
+                         kw.get("cs", L * 4), kw.get("values", FAKE), kw.get("vs", L * 64),
+                         ctypes.c_float(0.125), kw.get("splits", 1), kw.get("ws", None), kw.get("wsb", 0),
+                         kw.get("out", FAKE), None, None]
+    assert f(*args(L=0)) == E_SHAPE
+    assert f(*args(splits=-1)) == E_SHAPE
+    assert f(*args(lut=None)) == E_NULL
+    assert f(*args(cs=L * 4 - 16)) == E_SHAPE
+    assert f(*args(vs=L * 64 + 4)) == E_ALIGN
+    assert f(*args(codes=FAKE + 2)) == E_ALIGN
+    need = ws(ctypes.byref(s), L, 4)
+    assert need == 2 * 3 * 4 * (64 + 2) * 4
+    assert ws(ctypes.byref(s), L, 1) == 0
+    assert f(*args(splits=4)) == E_WS
+    assert f(*args(splits=4, ws=FAKE, wsb=need - 1)) == E_WS
+    assert b"workspace" in lib.lookat_last_error()
+    auto = lib.lookat_attend_decode_auto_splits(ctypes.byref(s), L)
+    assert auto >= 1 and ws(ctypes.byref(s), L, 0) == (0 if auto == 1 else 2 * 3 * auto * 66 * 4)
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2601_10155_amd import binding
+    cb = torch.zeros((1, 4, 256, 16))
+    with pytest.raises(ValueError):
+        binding.lookat_encode_keys(torch.zeros((1, 1, 4, 64)), cb)

@@ -1,0 +1,240 @@
+"""HIP path vs CPU oracle, element by element on the same seeded inputs, through the C ABI.
+
+Bars (written out here):
+  * codes: bit-exact;
+  * table entries and scores: |gpu - oracle| <= 1e-4 * (sum of the magnitudes of the summed terms)
+    (fp32 accumulation; relative to the summands so that cancellation is not penalised);
+  * outputs: |gpu - oracle| <= 2e-3 absolute (fp16 values, fp32 accumulation).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import lookat_inputs as li
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+OUT_ATOL = 2e-3
+REL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def lk():
+    import paper_2601_10155_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def assert_scores_close(s_gpu, lut, codes, s_ref):
+    """lut [B,H,m,K], codes [B,H,L,m]: tolerance relative to sum_i |lut[i][c_i]|."""
+    B, H, L, m = codes.shape
+    mag = np.zeros((B, H, L))
+    for i in range(m):
+        mag += np.abs(np.take_along_axis(lut[:, :, i, :].astype(np.float64), codes[..., i].astype(np.int64), axis=-1))
+    err = np.abs(s_gpu.astype(np.float64) - s_ref.astype(np.float64))
+    assert np.all(err <= REL * np.maximum(mag, 1e-6)), f"max score err {err.max()}"
+
+
+def assert_lut_close(lut_gpu, q, cb, lut_ref):
+    """q [B,H,T,d_k], cb [H,m,K,d_sub], lut [B,H,T,m,K]: tolerance relative to sum_j |q_j c_j|."""
+    B, H, T, d_k = q.shape
+    _, m, K, d_sub = cb.shape
+    qa = np.abs(q.astype(np.float64)).reshape(B, H, T, m, d_sub)
+    mag = np.einsum("bhtij,hicj->bhtic", qa, np.abs(cb.astype(np.float64)))
+    err = np.abs(lut_gpu.astype(np.float64) - lut_ref.astype(np.float64))
+    assert np.all(err <= REL * np.maximum(mag, 1e-6)), f"max lut err {err.max()}"
+
+
+# ---------------------------------------------------------------- encode --------------
+
+@pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (64, 16), (128, 8), (128, 16), (64, 64 // 64), (24, 2), (8, 8)])
+@pytest.mark.parametrize("key_dtype", ["float32", "float16"])
+def test_encode_bit_exact(lk, d_k, m, key_dtype):
+    cfg = li.shrink(li.CONFIGS["C2"], B=3, H=2, L=300 + m, d_k=d_k, m=m, n_calib=600, key_dtype=key_dtype,
+                    rank=min(8, d_k))
+    case = li.make_case(cfg, seed=1000 + d_k + m)
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 2)
+    ref = oracle.encode_keys(case["keys"], cb)
+    got = lk.lookat_encode_keys(dev(case["keys"]), dev(cb)).cpu().numpy()
+    assert got.dtype == np.uint8 and got.shape == ref.shape
+    assert np.array_equal(got, ref), f"{(got != ref).sum()} of {ref.size} codes differ"
+
+
+def test_encode_ties_and_duplicates(lk):
+    d_sub, K = 16, 256
+    rng = np.random.default_rng(4)
+    cb = (rng.standard_normal((2, 4, K, d_sub)) * 3).astype(np.float32)
+    cb[:, :, 9] = cb[:, :, 5]               # duplicate centroid: 9 may never be chosen
+    cb[0, 0, 100] = 0.0
+    cb[0, 0, 200] = 2.0                     # keys of all-ones are exactly midway between 100 and 200
+    cb[1] = 1.5                             # a head whose centroids are all equal -> code 0 everywhere
+    keys = rng.standard_normal((2, 2, 70, 64)).astype(np.float32)
+    keys[:, 0, :10, :16] = 1.0
+    keys[:, 0, 10:20, 16:32] = cb[0, 1, 5]  # exactly on the duplicated centroid
+    ref = oracle.encode_keys(keys, cb)
+    got = lk.lookat_encode_keys(dev(keys), dev(cb)).cpu().numpy()
+    assert np.array_equal(got, ref)
+    assert not (got == 9).any()
+    assert (got[:, 1] == 0).all()
+    assert (got[:, 0, 10:20, 1] == 5).all()
+
+
+def test_encode_append_into_cache(lk):
+    cfg = li.shrink(li.CONFIGS["C2"], B=2, H=3, L=5, n_calib=300)
+    case = li.make_case(cfg, seed=5)
+    cb = case["cb_init"]
+    ref = oracle.encode_keys(case["keys"], cb)
+    cache = torch.full((2, 3, 40, 4), 255, dtype=torch.uint8, device="cuda")
+    lk.lookat_encode_keys(dev(case["keys"]), dev(cb), cache=cache, position=16)
+    c = cache.cpu().numpy()
+    assert np.array_equal(c[:, :, 16:21], ref)
+    assert (c[:, :, :16] == 255).all() and (c[:, :, 21:] == 255).all()
+    # N = 0 is a no-op
+    empty = torch.empty((2, 3, 0, 64), device="cuda")
+    assert lk.lookat_encode_keys(empty, dev(cb)).shape == (2, 3, 0, 4)
+
+
+# ---------------------------------------------------------------- LUT ------------------
+
+@pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (128, 8), (128, 16), (64, 1), (24, 2)])
+@pytest.mark.parametrize("q_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("B,T", [(1, 1), (5, 1), (2, 37)])
+def test_build_lut_parity(lk, d_k, m, q_dtype, B, T):
+    cfg = li.shrink(li.CONFIGS["C2"], B=B, H=3, L=4, T=T, d_k=d_k, m=m, n_calib=300, q_dtype=q_dtype,
+                    rank=min(8, d_k))
+    case = li.make_case(cfg, seed=2000 + d_k + m + T)
+    cb = case["cb_init"]
+    ref = oracle.build_lut(case["q"], cb)
+    got = lk.lookat_build_lut(dev(case["q"]), dev(cb)).cpu().numpy()
+    assert got.shape == ref.shape
+    assert_lut_close(got, case["q"], cb, ref)
+
+
+# ---------------------------------------------------------------- decode ---------------
+
+def _decode_case(rng, B, H, L, d_k, m, lut_scale=2.0):
+    lut = (rng.standard_normal((B, H, m, 256)) * lut_scale).astype(np.float32)
+    codes = rng.integers(0, 256, size=(B, H, L, m), dtype=np.uint8)
+    v = rng.standard_normal((B, H, L, d_k)).astype(np.float16)
+    return lut, codes, v
+
+
+@pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (64, 8), (64, 16), (128, 8), (128, 16), (128, 2),
+                                   (64, 1), (128, 32), (32, 4), (256, 8), (40, 5), (96, 4)])
+@pytest.mark.parametrize("L", [1, 63, 64, 65, 257, 1000])
+def test_decode_parity_shapes(lk, d_k, m, L):
+    rng = np.random.default_rng(3000 + d_k * 7 + m * 3 + L)
+    B, H = 2, 5   # B*H = 10: not a multiple of the 8 dies
+    lut, codes, v = _decode_case(rng, B, H, L, d_k, m)
+    scale = 1.0 / math.sqrt(d_k)
+    ref, s_ref = oracle.attend_decode(lut, codes, v, scale, want_scores=True)
+    for splits in (0, 1, 3):
+        scores = torch.empty((B, H, L), dtype=torch.float32, device="cuda")
+        out = lk.lookat_attend_decode(dev(lut), dev(codes), dev(v), scale, num_splits=splits, scores_out=scores)
+        out = out.cpu().numpy()
+        assert np.isfinite(out).all()
+        assert np.max(np.abs(out - ref)) <= OUT_ATOL, f"splits={splits}: {np.max(np.abs(out - ref))}"
+        assert_scores_close(scores.cpu().numpy(), lut, codes, s_ref)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 3, 7, 16, 40])
+def test_decode_split_count_invariance(lk, splits):
+    """More ranges than 64-key tiles leaves some ranges empty: they must merge as zeros."""
+    rng = np.random.default_rng(77)
+    B, H, L, d_k, m = 1, 9, 777, 64, 4
+    lut, codes, v = _decode_case(rng, B, H, L, d_k, m, lut_scale=6.0)
+    ref = oracle.attend_decode(lut, codes, v, 0.125)
+    out = lk.lookat_attend_decode(dev(lut), dev(codes), dev(v), 0.125, num_splits=splits).cpu().numpy()
+    assert np.isfinite(out).all()
+    assert np.max(np.abs(out - ref)) <= OUT_ATOL
+
+
+def test_decode_peaked_and_flat_softmax(lk):
+    rng = np.random.default_rng(78)
+    B, H, L, d_k, m = 1, 2, 500, 64, 4
+    lut, codes, v = _decode_case(rng, B, H, L, d_k, m)
+    lut[0, 0] = 0.0
+    lut[0, 0, 0, 7] = 4000.0          # one-hot: a single key owns code 7 in subspace 0
+    codes[0, 0, :, 0] = 3
+    codes[0, 0, 321, 0] = 7
+    lut[0, 1] = -2.5                  # flat: output is the mean of the values
+    for splits in (1, 4):
+        out = lk.lookat_attend_decode(dev(lut), dev(codes), dev(v), 1.0, num_splits=splits).cpu().numpy()
+        assert np.max(np.abs(out[0, 0] - v[0, 0, 321].astype(np.float32))) <= 1e-6
+        assert np.max(np.abs(out[0, 1] - v[0, 1].astype(np.float64).mean(0))) <= OUT_ATOL
+    ref = oracle.attend_decode(lut, codes, v, 1.0)
+    assert np.max(np.abs(out - ref)) <= OUT_ATOL
+
+
+def test_decode_on_cache_views(lk):
+    """codes / values that are the first L rows of longer caches (strided (b,h) slabs)."""
+    rng = np.random.default_rng(79)
+    B, H, L, Lmax, d_k, m = 2, 3, 333, 512, 64, 4
+    lut, codes, v = _decode_case(rng, B, H, Lmax, d_k, m)
+    ref = oracle.attend_decode(lut, codes[:, :, :L], v[:, :, :L], 0.125)
+    out = lk.lookat_attend_decode(dev(lut), dev(codes)[:, :, :L], dev(v)[:, :, :L], 0.125).cpu().numpy()
+    assert np.max(np.abs(out - ref)) <= OUT_ATOL
+
+
+# ---------------------------------------------------------------- whole path -----------
+
+def _pipeline(lk, case, cb, scale, splits=0):
+    """encode -> table -> decode on the GPU; returns numpy codes, lut, scores, out."""
+    cfg = case["cfg"]
+    codes = lk.lookat_encode_keys(dev(case["keys"]), dev(cb))
+    lut = lk.lookat_build_lut(dev(case["q"]), dev(cb))
+    scores = torch.empty((cfg.B, cfg.H, cfg.L), dtype=torch.float32, device="cuda")
+    out = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, dev(case["values"]), scale,
+                                  num_splits=splits, scores_out=scores)
+    return codes.cpu().numpy(), lut.cpu().numpy(), scores.cpu().numpy(), out.cpu().numpy()
+
+
+def _check_pipeline(lk, case, cb, splits=0):
+    cfg = case["cfg"]
+    scale = 1.0 / math.sqrt(cfg.d_k)
+    codes_ref = oracle.encode_keys(case["keys"], cb)
+    lut_ref = oracle.build_lut(case["q"], cb)
+    codes, lut, scores, out = _pipeline(lk, case, cb, scale, splits)
+    assert np.array_equal(codes, codes_ref)
+    assert_lut_close(lut, case["q"], cb, lut_ref)
+    # downstream of the table each side consumes its own table (the whole path is compared)
+    out_ref, s_ref = oracle.attend_decode(lut_ref[:, :, 0], codes_ref, case["values"], scale, want_scores=True)
+    assert_scores_close(scores, lut_ref[:, :, 0], codes_ref, s_ref)
+    assert np.max(np.abs(out - out_ref)) <= OUT_ATOL
+    return out, out_ref
+
+
+def test_config_c0_whole_path(lk):
+    """Single head, d_k=64, N=256, m=4: codebooks from 10 Lloyd iterations started at the keys."""
+    case = li.make_case(li.CONFIGS["C0"], calib_is_cache=True)
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 10)
+    _check_pipeline(lk, case, cb)
+
+
+def test_config_c1_one_layer_whole_path(lk):
+    """GPT-2-small shape: 12 heads, d_k=64, context 1024, batch 1, m=2."""
+    case = li.make_case(li.CONFIGS["C1"])
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 3)
+    _check_pipeline(lk, case, cb)
+
+
+def test_config_c2_reduced_batch_whole_path(lk):
+    """GPT-2-small shape, m=4, context 1024, batch 4 of 32 (the oracle's share that runs in seconds)."""
+    case = li.make_case(li.shrink(li.CONFIGS["C2"], B=4, n_calib=1024))
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 2)
+    _check_pipeline(lk, case, cb, splits=4)
+
+
+def test_config_c3_reduced_whole_path(lk):
+    """Llama shape d_k=128, m=8 with a ragged long context and several ranges."""
+    case = li.make_case(li.shrink(li.CONFIGS["C3"], B=2, H=3, L=5000 + 37, n_calib=512))
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 1)
+    _check_pipeline(lk, case, cb, splits=0)
+    _check_pipeline(lk, case, cb, splits=5)

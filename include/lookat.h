@@ -113,7 +113,8 @@ int lookat_build_lut(const lookat_shape *shape, int32_t T,
  *   L               cached keys per (b,h), >= 1
  *   lut             [B,H,m,K] fp32, 16-byte aligned
  *   codes           element (b,h,l,i) at codes[(b*H+h)*code_stride_bh + l*m + i];
- *                   base pointer and code_stride_bh multiples of 16 bytes
+ *                   base pointer and code_stride_bh multiples of m bytes when m is
+ *                   2, 4, 8 or 16 (a key's codes are fetched with one load)
  *   values          fp16; element (b,h,l,j) at values[(b*H+h)*value_stride_bh + l*d_k + j];
  *                   base pointer 16-byte aligned, value_stride_bh >= L*d_k
  *   scale           softmax scale (Algorithm 1 uses 1/sqrt(d_k))

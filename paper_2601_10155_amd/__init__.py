@@ -15,10 +15,14 @@ from .binding import (  # noqa: F401
     last_error,
     lib_path,
     load_library,
+    lookat_attend_decode,
+    lookat_build_lut,
+    lookat_encode_keys,
     version,
 )
 
 __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
+    "lookat_attend_decode", "lookat_build_lut", "lookat_encode_keys",
 ]

@@ -445,9 +445,13 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     if (code_stride_bh < L * shape->m || value_stride_bh < L * shape->d_k)
         return fail(LOOKAT_ERR_SHAPE, "code_stride_bh=%lld / value_stride_bh=%lld smaller than one (b,h) slab",
                     (long long)code_stride_bh, (long long)value_stride_bh);
-    if (!aligned16(lut) || !aligned16(codes) || !aligned16(values) || !aligned16(out) || (code_stride_bh % 16) ||
-        ((value_stride_bh * 2) % 16))
-        return fail(LOOKAT_ERR_ALIGN, "lut, codes, values, out and the (b,h) strides must be 16-byte aligned");
+    if (!aligned16(lut) || !aligned16(values) || !aligned16(out) || ((value_stride_bh * 2) % 16))
+        return fail(LOOKAT_ERR_ALIGN, "lut, values, out and value_stride_bh must be 16-byte aligned");
+    // a key's m codes are fetched with one m-byte load when m is 2, 4, 8 or 16
+    const int cvec = (shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16) ? shape->m : 1;
+    if ((reinterpret_cast<uintptr_t>(codes) % cvec) || (code_stride_bh % cvec))
+        return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of %d bytes for m=%d", cvec,
+                    shape->m);
     if (scores_out && (reinterpret_cast<uintptr_t>(scores_out) & 3u))
         return fail(LOOKAT_ERR_ALIGN, "scores_out must be 4-byte aligned");
 

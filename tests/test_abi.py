@@ -83,6 +83,7 @@ def test_attend_decode_argument_errors(lib):
     assert f(*args(splits=-1)) == E_SHAPE
     assert f(*args(lut=None)) == E_NULL
     assert f(*args(cs=L * 4 - 16)) == E_SHAPE
+    assert f(*args(cs=L * 4 + 2)) == E_ALIGN
     assert f(*args(vs=L * 64 + 4)) == E_ALIGN
     assert f(*args(codes=FAKE + 2)) == E_ALIGN
     need = ws(ctypes.byref(s), L, 4)

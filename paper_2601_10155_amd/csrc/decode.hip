@@ -12,6 +12,8 @@
 //     (online softmax), so the streaming loop has no workgroup barrier;
 //   * the sequence is cut into `splits` ranges per (b,h) (flash-decoding style); the
 //     ranges are merged by a second small kernel.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace lookat {
@@ -53,57 +55,63 @@ __device__ __forceinline__ bool map_block(const DecodeArgs &a, int &bh, int &spl
     return bh < a.BH;
 }
 
-template <int M>
-struct CodeLoad;
-template <>
-struct CodeLoad<2> {
-    using type = uint16_t;
-};
-template <>
-struct CodeLoad<4> {
-    using type = uint32_t;
-};
-template <>
-struct CodeLoad<8> {
-    using type = uint2;
-};
-template <>
-struct CodeLoad<16> {
-    using type = uint4;
-};
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint32_t code_word(const uint16_t &c, int) { return c; }
-__device__ __forceinline__ uint32_t code_word(const uint32_t &c, int) { return c; }
-__device__ __forceinline__ uint32_t code_word(const uint2 &c, int w) { return w == 0 ? c.x : c.y; }
-__device__ __forceinline__ uint32_t code_word(const uint4 &c, int w)
+// Buffer descriptor over [base, base + bytes): loads past the end return zero instead of
+// faulting, which is how ragged tiles and the prefetch past the last tile are handled.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    return w == 0 ? c.x : (w == 1 ? c.y : (w == 2 ? c.z : c.w));
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
 }
 
-// Unscaled ADC score of one key.  M > 0: the key's m codes are loaded as one vector.
+// The m codes of one key, fetched with a single load when m is 2, 4, 8 or 16.
 template <int M>
-__device__ __forceinline__ float adc_score(const float *lut_s, const uint8_t *code_ptr, int /*m*/)
-{
-    using CT = typename CodeLoad<M>::type;
-    const CT c = *reinterpret_cast<const CT *>(code_ptr);
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < M; ++i) {
-        const uint32_t byte = (code_word(c, i / 4) >> (8 * (i % 4))) & 0xffu;
-        s += lut_s[i * kCentroids + byte];
+struct KeyCodes {
+    static constexpr int kWords = (M + 3) / 4;
+    uint32_t w[kWords];
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rc, uint32_t byte_off)
+    {
+        if constexpr (M == 2) {
+            w[0] = __builtin_amdgcn_raw_buffer_load_b16(rc, byte_off, 0, 0);
+        } else if constexpr (M == 4) {
+            w[0] = __builtin_amdgcn_raw_buffer_load_b32(rc, byte_off, 0, 0);
+        } else if constexpr (M == 8) {
+            const v2u t = __builtin_amdgcn_raw_buffer_load_b64(rc, byte_off, 0, 0);
+            w[0] = t.x;
+            w[1] = t.y;
+        } else {
+            static_assert(M == 16, "vector code loads exist for m = 2, 4, 8, 16");
+            const v4u t = __builtin_amdgcn_raw_buffer_load_b128(rc, byte_off, 0, 0);
+            w[0] = t.x;
+            w[1] = t.y;
+            w[2] = t.z;
+            w[3] = t.w;
+        }
     }
-    return s;
-}
-template <>
-__device__ __forceinline__ float adc_score<0>(const float *lut_s, const uint8_t *code_ptr, int m)
+    // Unscaled ADC score: sum_i LUT_i[code_i], i ascending.
+    __device__ __forceinline__ float score(const float *lut_s) const
+    {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < M; ++i) {
+            const uint32_t byte = (w[i / 4] >> (8 * (i % 4))) & 0xffu;
+            s += lut_s[i * kCentroids + byte];
+        }
+        return s;
+    }
+};
+
+// Runtime m: byte loads (used for m = 1 and m = 32 and any m without a vector load).
+__device__ __forceinline__ float score_bytes(const float *lut_s, __amdgpu_buffer_rsrc_t rc, uint32_t byte_off, int m)
 {
     float s = 0.f;
     for (int i = 0; i < m; ++i)
-        s += lut_s[i * kCentroids + code_ptr[i]];
+        s += lut_s[i * kCentroids + __builtin_amdgcn_raw_buffer_load_b8(rc, byte_off + i, 0, 0)];
     return s;
 }
 
-__device__ __forceinline__ void fma_row(float (&acc)[8], float p, const uint4 &v)
+__device__ __forceinline__ void fma_row(float (&acc)[8], float p, const v4u &v)
 {
     const __half2 *h = reinterpret_cast<const __half2 *>(&v);
 #pragma unroll
@@ -114,34 +122,99 @@ __device__ __forceinline__ void fma_row(float (&acc)[8], float p, const uint4 &v
     }
 }
 
-// Loads CH consecutive wave-wide row groups of a tile, starting at group g0; rows past the
-// end of the range read as zero.
-template <int DK, int CH>
-__device__ __forceinline__ void load_rows(uint4 (&v)[CH], const __half *values_bh, int64_t kb, int64_t k1, int g0,
-                                          int rowin, int sub)
+// acc += p_j * row_j for the CH row groups c0 .. c0+CH-1 held in v; p_j is the weight held by
+// lane c0+j of the caller's LPR-lane group.
+template <int LPR, int CH, int J = 0>
+__device__ __forceinline__ void fma_rows(float (&acc)[8], float p, const v4u (&v)[CH], int c0)
 {
-    constexpr int RPL = kWave / (DK / 8);
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int64_t row = kb + (g0 + j) * RPL + rowin;
-        v[j] = make_uint4(0u, 0u, 0u, 0u);
-        if (row < k1)
-            v[j] = *reinterpret_cast<const uint4 *>(values_bh + row * DK + sub * 8);
+    if constexpr (J < CH) {
+        // c0 is 0 or 8 (CH = 8 whenever a tile has more than one chunk)
+        float pj;
+        if constexpr (LPR <= 8) {
+            pj = group_broadcast<LPR, J>(p);
+        } else {
+            pj = (c0 == 0) ? group_broadcast<LPR, J>(p)
+               : (c0 == 8) ? group_broadcast<LPR, (J + 8) % LPR>(p)
+               : (c0 == 16) ? group_broadcast<LPR, (J + 16) % LPR>(p)
+                            : group_broadcast<LPR, (J + 24) % LPR>(p);
+        }
+        fma_row(acc, pj, v[J]);
+        fma_rows<LPR, CH, J + 1>(acc, p, v, c0);
     }
 }
 
-// DK in {32, 64, 128, 256}; M in {2, 4, 8, 16} or 0 (= runtime m, byte loads).
-template <int DK, int M>
-__global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a)
+// Loads CH consecutive wave-wide row groups of the tile starting at key kb, from group g0.
+template <int DK, int CH>
+__device__ __forceinline__ void load_rows(v4u (&v)[CH], __amdgpu_buffer_rsrc_t rv, uint32_t kb, int g0, int lane)
+{
+    // lane (rowin, sub) reads 16 bytes at row*DK*2 + sub*16 = (row0*DK*2) + lane*16: 1 KB per load
+    constexpr uint32_t kGroupBytes = kWave * 16;
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+        v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, kb * (DK * 2) + (g0 + j) * kGroupBytes + lane * 16, 0, 0);
+}
+
+// Online-softmax state of one wavefront (base-2 exponent domain).
+struct SoftmaxState {
+    float m_run = -INFINITY;   // running max of scale*log2e*s over the keys seen so far
+    float z = 0.f;             // this lane's share of the running sum of weights
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // this lane's slice of sum_l w_l v_l
+};
+
+// One 64-key tile of a wavefront: its codes (kc) and first CH value-row groups (v) are in
+// registers or in flight.  Scores one key per lane (key = kb + kofs), updates the running
+// max / sum, and accumulates the weighted value rows.
+template <int DK, int M, int CH>
+__device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &st, const KeyCodes<M ? M : 4> &kc,
+                                             v4u (&v)[CH], const float *lut_s, __amdgpu_buffer_rsrc_t rc,
+                                             __amdgpu_buffer_rsrc_t rv, int bh, uint32_t kb, uint32_t k1,
+                                             uint32_t kofs, int lane, int m)
+{
+    constexpr int LPR = DK / 8;
+    constexpr int NLD = LPR;
+    const uint32_t key = kb + kofs;
+    float raw;
+    if constexpr (M != 0)
+        raw = kc.score(lut_s);
+    else
+        raw = score_bytes(lut_s, rc, key * m, m);
+    float s = -INFINITY;
+    if (key < k1) {
+        if (a.scores_out)
+            a.scores_out[(int64_t)bh * a.L + key] = raw;
+        s = raw * a.scale_log2e;
+    }
+    const float m_new = fmaxf(st.m_run, wave_max(s));
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float corr = fast_exp2(st.m_run - m_use);
+    const float p = fast_exp2(s - m_use);
+    st.z = st.z * corr + p;
+#pragma unroll
+    for (int d = 0; d < 8; ++d)
+        st.acc[d] *= corr;
+    st.m_run = m_new;
+#pragma unroll
+    for (int c0 = 0; c0 < NLD; c0 += CH) {
+        fma_rows<LPR, CH>(st.acc, p, v, c0);
+        if (c0 + CH < NLD)
+            load_rows<DK, CH>(v, rv, kb, c0 + CH, lane);   // next row groups of this tile
+    }
+}
+
+// DK in {32, 64, 128, 256}; M in {2, 4, 8, 16} or 0 (= runtime m, byte loads);
+// WAVES wavefronts per workgroup, OCC = wavefronts per SIMD the register budget must allow.
+template <int DK, int M, int WAVES, int OCC>
+__global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const DecodeArgs a)
 {
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
     constexpr int RPL = kWave / LPR;       // value rows covered by one wave-wide load
     constexpr int NLD = kTile / RPL;       // wave-wide loads per tile (= LPR)
     constexpr int CH = NLD < 8 ? NLD : 8;  // loads kept in flight together
+    constexpr int NT = WAVES * kWave;
 
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                                   // [m][256]
-    float *red_s = smem + (M ? M : a.m) * kCentroids;      // [kDecWaves][DK + 2]
+    float *red_s = smem + (M ? M : a.m) * kCentroids;      // [WAVES][DK + 2]
 
     int bh, split;
     if (!map_block(a, bh, split))
@@ -151,77 +224,71 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
 
-    {   // stage the table of this (b,h): m KB, 16 bytes per thread per step
-        const float4 *g = reinterpret_cast<const float4 *>(a.lut + (int64_t)bh * m * kCentroids);
-        float4 *s4 = reinterpret_cast<float4 *>(lut_s);
-        for (int x = tid; x < m * (kCentroids / 4); x += kDecThreads)
-            s4[x] = g[x];
-    }
-    __syncthreads();
+    const uint32_t k0 = (uint32_t)split * (uint32_t)a.keys_per_split;
+    const uint32_t k1 = (k0 + a.keys_per_split < a.L) ? (uint32_t)(k0 + a.keys_per_split) : (uint32_t)a.L;
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(a.values + (int64_t)bh * a.value_stride, k1 * (uint32_t)(DK * 2));
+    const __amdgpu_buffer_rsrc_t rc = make_rsrc(a.codes + (int64_t)bh * a.code_stride, k1 * (uint32_t)m);
 
-    const int64_t k0 = (int64_t)split * a.keys_per_split;
-    const int64_t k1 = (k0 + a.keys_per_split < a.L) ? (k0 + a.keys_per_split) : a.L;
-    const uint8_t *codes_bh = a.codes + (int64_t)bh * a.code_stride;
-    const __half *values_bh = a.values + (int64_t)bh * a.value_stride;
+    // Everything the first tile needs is requested before anything is waited for, in the
+    // order it is needed (loads return in order, so each wait below covers only what precedes):
+    // 1) this thread's slice of the table (staged through registers: the wait before the
+    //    barrier then covers the table alone, not the value rows behind it);
+    const float4 *lut_g = reinterpret_cast<const float4 *>(a.lut + (int64_t)bh * m * kCentroids);
+    constexpr int kLutRegs = M ? (M * (kCentroids / 4) + NT - 1) / NT : 1;
+    float4 lut_r[kLutRegs];
+    if constexpr (M != 0) {
+#pragma unroll
+        for (int x = 0; x < kLutRegs; ++x)
+            if (tid + x * NT < M * (kCentroids / 4))
+                lut_r[x] = lut_g[tid + x * NT];
+    }
+    // 2) the codes of the wave's first tile;  3) its value rows.
+    // Lane (rowin, sub) holds the value rows RPL*j + rowin, j = 0..NLD-1, of a tile.  It scores
+    // the key RPL*sub + rowin, so the NLD weights a lane needs sit in its own group of LPR
+    // consecutive lanes and are fetched with DPP moves instead of LDS shuffles.
     const int sub = lane % LPR;      // which 8-coordinate slice of the value row
     const int rowin = lane / LPR;    // which row of a wave-wide load
-
-    float m_run = -INFINITY;         // running max of scale*log2e*s over this wave's keys
-    float z = 0.f;                   // per-lane share of the running sum
-    float acc[8];
+    const uint32_t kofs = (uint32_t)(RPL * sub + rowin);
+    uint32_t kb = k0 + (uint32_t)wave * kTile;
+    KeyCodes<M ? M : 4> kc;
+    if constexpr (M != 0)
+        kc.load(rc, (kb + kofs) * M);
+    v4u v[CH];
+    load_rows<DK, CH>(v, rv, kb, 0, lane);
+    {
+        float4 *s4 = reinterpret_cast<float4 *>(lut_s);
+        if constexpr (M != 0) {
 #pragma unroll
-    for (int d = 0; d < 8; ++d)
-        acc[d] = 0.f;
-
-    for (int64_t kb = k0 + (int64_t)wave * kTile; kb < k1; kb += (int64_t)kDecWaves * kTile) {
-        // value rows of the tile: LPR lanes per row, RPL rows per wave-wide load.  The first
-        // group of loads is issued before the score phase so that its latency is covered.
-        uint4 v[CH];
-        load_rows<DK, CH>(v, values_bh, kb, k1, 0, rowin, sub);
-
-        // ---- score phase: lane = key ----
-        const int64_t key = kb + lane;
-        float s = -INFINITY;
-        if (key < k1) {
-            const float raw = adc_score<M>(lut_s, codes_bh + key * m, m);
-            if (a.scores_out)
-                a.scores_out[(int64_t)bh * a.L + key] = raw;
-            s = raw * a.scale_log2e;
-        }
-        const float m_new = fmaxf(m_run, wave_max(s));
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = fast_exp2(m_run - m_use);
-        const float p = fast_exp2(s - m_use);
-        z = z * corr + p;
-#pragma unroll
-        for (int d = 0; d < 8; ++d)
-            acc[d] *= corr;
-        m_run = m_new;
-
-        // ---- value phase ----
-#pragma unroll
-        for (int c0 = 0; c0 < NLD; c0 += CH) {
-            uint4 w[CH];
-#pragma unroll
-            for (int j = 0; j < CH; ++j)
-                w[j] = v[j];
-            if (c0 + CH < NLD)
-                load_rows<DK, CH>(v, values_bh, kb, k1, c0 + CH, rowin, sub);
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const float pj = __shfl(p, (c0 + j) * RPL + rowin);
-                fma_row(acc, pj, w[j]);
-            }
+            for (int x = 0; x < kLutRegs; ++x)
+                if (tid + x * NT < M * (kCentroids / 4))
+                    s4[tid + x * NT] = lut_r[x];
+        } else {
+            for (int x = tid; x < m * (kCentroids / 4); x += NT)
+                s4[x] = lut_g[x];
         }
     }
+    __syncthreads();   // table complete in LDS (the value rows stay in flight)
+
+    // First tile (requested above), then the wave's remaining tiles: request, consume.  Tiles
+    // are requested only if they exist (a load past the range would return zero but still
+    // occupy the address pipeline), and a tile's registers are dead at the loop back-edge.
+    SoftmaxState st;
+    if (kb < k1) {
+        consume_tile<DK, M, CH>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m);
+        for (kb += NT; kb < k1; kb += NT) {
+            if constexpr (M != 0)
+                kc.load(rc, (kb + kofs) * M);
+            load_rows<DK, CH>(v, rv, kb, 0, lane);
+            consume_tile<DK, M, CH>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m);
+        }
+    }
+    float m_run = st.m_run, z = st.z;
+    float(&acc)[8] = st.acc;
 
     // ---- fold the rows of the wave, then the waves of the workgroup ----
 #pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) {
-#pragma unroll
-        for (int d = 0; d < 8; ++d)
-            acc[d] += __shfl_xor(acc[d], off);
-    }
+    for (int d = 0; d < 8; ++d)
+        acc[d] = sum_over_lane_classes<LPR>(acc[d]);
     z = wave_sum(z);
     float *mine = red_s + wave * (DK + 2);
     if (lane < LPR) {
@@ -238,12 +305,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     if (tid < DK) {
         float mx = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w)
+        for (int w = 0; w < WAVES; ++w)
             mx = fmaxf(mx, red_s[w * (DK + 2) + DK]);
         const float m_use = (mx == -INFINITY) ? 0.f : mx;
         float o = 0.f, zz = 0.f;
 #pragma unroll
-        for (int w = 0; w < kDecWaves; ++w) {
+        for (int w = 0; w < WAVES; ++w) {
             const float wgt = fast_exp2(red_s[w * (DK + 2) + DK] - m_use);
             o = fmaf(wgt, red_s[w * (DK + 2) + tid], o);
             zz = fmaf(wgt, red_s[w * (DK + 2) + DK + 1], zz);
@@ -292,7 +359,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_generic_kernel(const
         const int64_t key = kb + tid;
         float s = -INFINITY;
         if (key < k1) {
-            const float raw = adc_score<0>(lut_s, codes_bh + key * m, m);
+            float raw = 0.f;
+            for (int i = 0; i < m; ++i)
+                raw += lut_s[i * kCentroids + codes_bh[key * m + i]];
             if (a.scores_out)
                 a.scores_out[(int64_t)bh * a.L + key] = raw;
             s = raw * a.scale_log2e;
@@ -365,11 +434,13 @@ static int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 
 static int auto_splits(const lookat_shape *s, int64_t L)
 {
-    // aim at >= ~4 workgroups per compute unit, but never ranges shorter than one
-    // 64-key tile per wavefront
+    // One range per (b,h) as long as the (b,h) count alone fills the 256 compute units: the
+    // merge kernel is a second launch and costs more than it buys on short contexts.  With
+    // few (b,h) pairs the sequence is cut so that about 512 workgroups exist, but never into
+    // ranges shorter than 1024 keys.
     const int64_t BH = (int64_t)s->B * s->H;
-    int64_t want = (1024 + BH - 1) / BH;
-    int64_t cap = (L + kDecWaves * kTile - 1) / (kDecWaves * kTile);
+    int64_t want = 512 / BH;
+    const int64_t cap = (L + 1023) / 1024;
     if (want > cap)
         want = cap;
     if (want < 1)
@@ -381,27 +452,43 @@ static int auto_splits(const lookat_shape *s, int64_t L)
 
 static bool tuned_dk(int d_k) { return d_k == 32 || d_k == 64 || d_k == 128 || d_k == 256; }
 
-template <int DK>
-static void launch_tuned(const DecodeArgs &a, dim3 grid, size_t lds, hipStream_t st)
+template <int DK, int WAVES, int OCC>
+static void launch_tuned(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
-    dim3 block(kDecThreads);
+    dim3 block(WAVES * kWave);
+    const size_t lds = ((size_t)a.m * kCentroids + (size_t)WAVES * (DK + 2)) * sizeof(float);
     switch (a.m) {
     case 2:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, WAVES, OCC>), grid, block, lds, st, a);
         break;
     case 4:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 4>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, WAVES, OCC>), grid, block, lds, st, a);
         break;
     case 8:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 8>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, WAVES, OCC>), grid, block, lds, st, a);
         break;
     case 16:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 16>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, WAVES, OCC>), grid, block, lds, st, a);
         break;
     default:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 0>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 0, WAVES, OCC>), grid, block, lds, st, a);
         break;
     }
+}
+
+// Wavefronts per workgroup: 16 for long ranges (at least 32 tiles), else 4 (measured on
+// MI355X: the small workgroup wins at context 1024, the large one from 16K keys on).
+static int pick_waves(int d_k, int m, int64_t keys_per_split)
+{
+    static const int forced = [] {
+        const char *e = getenv("LOOKAT_DECODE_WAVES");
+        return e ? atoi(e) : 0;
+    }();
+    if ((d_k != 64 && d_k != 128) || (m != 2 && m != 4 && m != 8))
+        return 4;   // the 16-wave variant must fit 64 registers; only these shapes do
+    if (forced == 4 || forced == 16 || (forced == 8 && d_k == 64))
+        return forced;
+    return keys_per_split >= 32 * kTile ? 16 : 4;
 }
 
 }  // namespace lookat
@@ -455,6 +542,9 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     if (scores_out && (reinterpret_cast<uintptr_t>(scores_out) & 3u))
         return fail(LOOKAT_ERR_ALIGN, "scores_out must be 4-byte aligned");
 
+    // kernels address one (b,h) slab with 32-bit byte offsets (plus one tile of prefetch)
+    if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
     const int64_t BH = (int64_t)shape->B * shape->H;
     const int S = num_splits ? num_splits : auto_splits(shape, L);
     const size_t need = (S == 1) ? 0 : (size_t)BH * S * (shape->d_k + 2) * sizeof(float);
@@ -490,19 +580,27 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)nblocks);
     if (tuned_dk(shape->d_k)) {
-        const size_t lds = ((size_t)shape->m * kCentroids + (size_t)kDecWaves * (shape->d_k + 2)) * sizeof(float);
+        const int waves = pick_waves(shape->d_k, shape->m, a.keys_per_split);
         switch (shape->d_k) {
         case 32:
-            launch_tuned<32>(a, grid, lds, st);
+            launch_tuned<32, 4, 4>(a, grid, st);
             break;
         case 64:
-            launch_tuned<64>(a, grid, lds, st);
+            if (waves == 16)
+                launch_tuned<64, 16, 8>(a, grid, st);
+            else if (waves == 8)
+                launch_tuned<64, 8, 8>(a, grid, st);
+            else
+                launch_tuned<64, 4, 4>(a, grid, st);
             break;
         case 128:
-            launch_tuned<128>(a, grid, lds, st);
+            if (waves == 16)
+                launch_tuned<128, 16, 8>(a, grid, st);
+            else
+                launch_tuned<128, 4, 4>(a, grid, st);
             break;
         default:
-            launch_tuned<256>(a, grid, lds, st);
+            launch_tuned<256, 4, 4>(a, grid, st);
             break;
         }
     } else {

@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""LOOKAT decode benchmark on one MI355X.
+
+A "step" is one pass of the decode hot path over every layer of the workload: per layer,
+encode the new token's key into the code cache (lookat_encode_keys), build the query's
+lookup tables (lookat_build_lut), attend over the coded cache (lookat_attend_decode).
+Inputs are seeded and synthetic (lookat_inputs), resident in HBM before the timed region;
+codebooks come from the library's own Lloyd iterations on seeded calibration keys.
+
+Prints ONE JSON line: whole-step throughput in keys scored per second, the HBM roofline
+of the decode kernel (algorithmic code+value bytes / average launch duration, measured
+with HIP events on the launch stream) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
+                    help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
+    ap.add_argument("--kmeans-iters", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device state of one attention layer: codebooks, code cache, value cache, query, new key."""
+
+    def __init__(self, lk, li, cfg, device, index, kmeans_iters):
+        import torch
+        case = li.torch_case(cfg, device, layer=index)
+        self.cb = lk.lookat_kmeans(case["calib"], case["cb_init"], kmeans_iters)
+        self.codes = lk.lookat_encode_keys(case["keys"], self.cb)           # [B,H,L,m] code cache
+        self.new_key = case["keys"][:, :, cfg.L - 1:cfg.L].contiguous()      # the step's new token
+        self.values = case["values"]
+        self.q = case["q"]
+        self.lut = torch.empty((cfg.B, cfg.H, 1, cfg.m, cfg.K), dtype=torch.float32, device=device)
+        self.out = torch.empty((cfg.B, cfg.H, cfg.d_k), dtype=torch.float32, device=device)
+        self.host_keys_last = None
+        del case
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import lookat_inputs as li
+    import paper_2601_10155_amd as lk
+
+    if not torch.cuda.is_available():
+        print("bench.py needs an MI355X; no GPU is visible", file=sys.stderr)
+        sys.exit(1)
+    lk.load_library()   # raises if liblookat.so is not built: there is no fallback path
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+
+    cfg = li.CONFIGS[args.workload]
+    scale = 1.0 / math.sqrt(cfg.d_k)
+    layers = [Layer(lk, li, cfg, device, i, args.kmeans_iters) for i in range(cfg.layers)]
+    splits = lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L)
+    ws_bytes = lk.attend_decode_workspace_bytes(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, splits)
+    workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
+    torch.cuda.synchronize()
+
+    def decode_only(ly):
+        lk.lookat_attend_decode(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
+                                num_splits=splits, workspace=workspace, out=ly.out)
+
+    def step():
+        for ly in layers:
+            lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
+            lk.lookat_build_lut(ly.q, ly.cb, lut_out=ly.lut)
+            decode_only(ly)
+
+    # ---- one eager step: its outputs are the reference for the graph replays ----------
+    step()
+    torch.cuda.synchronize()
+    eager_out = [ly.out.clone() for ly in layers]
+
+    run_step = step
+    graph = None
+    if args.mode == "graph":
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                      # warm the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+        for _ in range(2):              # replays must reproduce the eager step exactly
+            for ly in layers:
+                ly.out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            for ly, ref in zip(layers, eager_out):
+                if not torch.equal(ly.out, ref):
+                    raise RuntimeError("graph replay differs from the eager step")
+
+    # ---- timed region: W warm-up steps, then exactly K steps ----------------------------
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    keys_per_step = cfg.layers * cfg.B * cfg.H * cfg.L
+    value = keys_per_step * args.steps / elapsed
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # ---- roofline of the dominant kernel: decode launches alone, back to back, rotating over
+    #      the layers' distinct caches (so no launch re-reads what the last-level cache holds) ----
+    bytes_per_launch = cfg.B * cfg.H * cfg.L * (cfg.m + 2 * cfg.d_k)
+    n_launch = max(args.steps, 20) * cfg.layers
+    for ly in layers:
+        decode_only(ly)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(n_launch):
+        decode_only(layers[i % cfg.layers])
+    e1.record()
+    torch.cuda.synchronize()
+    us_per_launch = e0.elapsed_time(e1) * 1e3 / n_launch
+    achieved = bytes_per_launch / us_per_launch / 1e3   # GB/s
+
+    # plain read stream over the same value caches: what the HBM read path delivers here
+    sink = torch.zeros(4, dtype=torch.int32, device=device)
+    for ly in layers:
+        lk.lookat_probe_stream_read(ly.values, sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n_launch):
+        lk.lookat_probe_stream_read(layers[i % cfg.layers].values, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_us = e0.elapsed_time(e1) * 1e3 / n_launch
+    stream_gbs = layers[0].values.numel() * 2 / stream_us / 1e3
+
+    result = {
+        "metric": "LUT-attention decode keys scored/sec/GPU; achieved HBM GB/s vs peak",
+        "value": value,
+        "unit": "keys/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d_k={cfg.d_k} m={cfg.m} K={cfg.K} "
+                        f"layers={cfg.layers}; per layer encode(1 new key) + build_lut + attend_decode",
+            "values": "fp16", "codes": "u8", "lut": "f32", "launch": args.mode, "num_splits": splits,
+            "codebooks": f"{args.kmeans_iters} Lloyd iterations (lookat_kmeans_step) on {cfg.n_calib} seeded "
+                         "calibration keys per head",
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "lookat::decode_split_kernel",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_launch": bytes_per_launch,
+            "us_per_launch": us_per_launch,
+            "launches_timed": n_launch,
+            "read_stream_GBs": stream_gbs,
+            "frac_of_read_stream": achieved / stream_gbs,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, layers, scale, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, layers, scale, budget_s):
+    """The CPU oracle as it stands, on the same arrays the GPU consumed: the same three calls
+    (encode the new key, build the tables, attend) on whole (b,h) slabs of the first layer,
+    as many batch entries as fit the time budget.  Also checks the GPU output on that sample."""
+    import numpy as np
+
+    import oracle
+
+    ly = layers[0]
+    nb = cfg.B
+    codes = ly.codes.cpu().numpy()
+    values = ly.values.cpu().numpy()
+    q = ly.q.cpu().numpy()
+    cb = ly.cb.cpu().numpy()
+    new_key = ly.new_key.cpu().numpy()
+    gpu_out = ly.out.cpu().numpy()
+    threads = oracle.num_threads()
+
+    def once(n):
+        c = codes[:n].copy()
+        c[:, :, cfg.L - 1:cfg.L] = oracle.encode_keys(new_key[:n], cb)
+        lut = oracle.build_lut(q[:n], cb)
+        return oracle.attend_decode(lut[:, :, 0], c, values[:n], scale)
+
+    # size the sample: time one batch entry, then take as many as fit the budget
+    t0 = time.perf_counter()
+    once(1)
+    t1 = time.perf_counter() - t0
+    n = int(max(1, min(nb, budget_s / max(t1, 1e-6) / 2)))
+    reps = 0
+    t0 = time.perf_counter()
+    while True:
+        out = once(n)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min(budget_s, 2.0) or reps >= 50:
+            break
+    keys = reps * n * cfg.H * cfg.L
+    err = float(np.max(np.abs(out - gpu_out[:n])))
+    return {
+        "value": keys / dt,
+        "unit": "keys/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"layer 0, batch entries 0..{n - 1} of {cfg.B} (all {cfg.H} heads, L={cfg.L}), "
+                  f"{reps} repetitions, fp64, OpenMP over (b,h)",
+        "max_abs_diff_gpu_vs_oracle": err,
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -142,6 +142,27 @@ int lookat_attend_decode(const lookat_shape *shape, int64_t L,
  * no HIP call); 0 if the shape is invalid. */
 int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);
 
+/*
+ * One Lloyd iteration of codebook learning (paper Sec. 3.4, "Prototype Learning":
+ * k-means with K = 256 per subspace on a set of calibration keys).  Every calibration
+ * sub-vector is assigned to its nearest centroid by the rule of lookat_encode_keys;
+ * each centroid then moves to the mean of its members, computed as an fp64 sum in
+ * ascending key order, divided by the count and rounded to fp32.  A centroid without
+ * members keeps its value.  The result is reproducible bit for bit.
+ *
+ *   shape          B must be 1 (one calibration set per head)
+ *   Nc             calibration keys per head, >= 1
+ *   calib          [H,Nc,d_k] fp32, 16-byte aligned
+ *   codebooks_in   [H,m,K,d_sub] fp32, 16-byte aligned
+ *   codebooks_out  same shape; must not alias codebooks_in
+ *   assign         out [H,Nc,m] uint8: the assignment made against codebooks_in
+ */
+int lookat_kmeans_step(const lookat_shape *shape, int64_t Nc,
+                       const float *calib,
+                       const float *codebooks_in, float *codebooks_out,
+                       uint8_t *assign,
+                       void *stream);
+
 /* Host pointer to a thread-local, NUL-terminated description of the last
  * failure on this thread; valid until the next library call on this thread. */
 const char *lookat_last_error(void);

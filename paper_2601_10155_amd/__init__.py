@@ -18,11 +18,15 @@ from .binding import (  # noqa: F401
     lookat_attend_decode,
     lookat_build_lut,
     lookat_encode_keys,
+    lookat_kmeans,
+    lookat_kmeans_step,
+    lookat_probe_stream_read,
     version,
 )
 
 __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
-    "lookat_attend_decode", "lookat_build_lut", "lookat_encode_keys",
+    "lookat_attend_decode", "lookat_build_lut", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
+    "lookat_probe_stream_read",
 ]

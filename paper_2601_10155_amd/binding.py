@@ -54,6 +54,10 @@ def load_library():
         lib.lookat_attend_decode_auto_splits.restype = i32
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
+        lib.lookat_kmeans_step.restype = ctypes.c_int
+        lib.lookat_probe_stream_read.argtypes = [vp, sz, vp, vp]
+        lib.lookat_probe_stream_read.restype = ctypes.c_int
         lib.lookat_last_error.restype = ctypes.c_char_p
         lib.lookat_version.restype = ctypes.c_int
         _lib = lib
@@ -207,6 +211,48 @@ def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.T
                                     out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
                                     _stream(values)))
     return out
+
+
+def lookat_kmeans_step(calib: torch.Tensor, codebooks: torch.Tensor, codebooks_out: torch.Tensor | None = None,
+                       assign_out: torch.Tensor | None = None):
+    """One Lloyd iteration. calib [H,Nc,d_k] fp32, codebooks [H,m,256,d_sub] fp32 ->
+    (new codebooks, assignment [H,Nc,m] uint8 against the input codebooks)."""
+    lib = load_library()
+    calib = _dev(calib, "calib").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    H, Nc, d_k = calib.shape
+    Hc, m, K, d_sub = cb.shape
+    if Hc != H or m * d_sub != d_k or cb.dtype != torch.float32 or calib.dtype != torch.float32:
+        raise ValueError("calib must be fp32 [H,Nc,d_k] and codebooks fp32 [H,m,K,d_k/m]")
+    if codebooks_out is None:
+        codebooks_out = torch.empty_like(cb)
+    if assign_out is None:
+        assign_out = torch.empty((H, Nc, m), dtype=torch.uint8, device=calib.device)
+    shape = _Shape(1, H, d_k, m, K)
+    _check(lib.lookat_kmeans_step(ctypes.byref(shape), Nc, calib.data_ptr(), cb.data_ptr(), codebooks_out.data_ptr(),
+                                  assign_out.data_ptr(), _stream(calib)))
+    return codebooks_out, assign_out
+
+
+def lookat_kmeans(calib: torch.Tensor, codebooks: torch.Tensor, iters: int) -> torch.Tensor:
+    """`iters` Lloyd iterations from the given initial codebooks (ping-pong between two buffers)."""
+    cur = codebooks.contiguous().clone()
+    nxt = torch.empty_like(cur)
+    assign = torch.empty((calib.shape[0], calib.shape[1], cur.shape[1]), dtype=torch.uint8, device=calib.device)
+    for _ in range(int(iters)):
+        lookat_kmeans_step(calib, cur, nxt, assign)
+        cur, nxt = nxt, cur
+    return cur
+
+
+def lookat_probe_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """Measurement aid: streams all bytes of `src` once through a plain read kernel."""
+    lib = load_library()
+    _dev(src, "src"), _dev(sink, "sink")
+    if not src.is_contiguous():
+        raise ValueError("src must be contiguous")
+    _check(lib.lookat_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                        _stream(src)))
 
 
 # short aliases

@@ -113,6 +113,133 @@ __global__ __launch_bounds__(kEncThreads) void encode_generic_kernel(const KT *_
     codes[bh * code_stride_bh + n * m + i] = (uint8_t)best_c;
 }
 
+// ---- few keys per head (decode-time append) -------------------------------------------
+// With a handful of keys per head the thread-per-key kernel above leaves the chip empty and
+// each thread walks all 256 centroids serially.  Here the centroids are spread over the
+// threads instead: one block = one (head, subspace) and up to kEncFewKeys keys; thread c
+// holds centroid c in registers as fp64, evaluates its distance to every key of the block
+// (same arithmetic, same order) and the block takes the argmin over (distance, index).
+constexpr int kEncFewKeys = 8;
+
+// Total order that reproduces the serial scan: smaller distance first, then smaller index.
+// Distances are sums of squares (>= +0), so their bit patterns order like the values; a NaN
+// maps above everything except at centroid 0, where it maps below everything (the serial
+// scan starts from centroid 0 and no later distance compares below a NaN).
+__device__ __forceinline__ uint64_t dist_order_key(double d, int c)
+{
+    if (d != d)
+        return c == 0 ? 0ull : ~0ull;
+    return (uint64_t)__double_as_longlong(d);
+}
+
+__device__ __forceinline__ void argmin_merge(uint64_t &k, int &c, uint64_t k2, int c2)
+{
+    if (k2 < k || (k2 == k && c2 < c)) {
+        k = k2;
+        c = c2;
+    }
+}
+
+template <typename KT, int DSUB>
+__global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__restrict__ keys,
+                                                                const float *__restrict__ codebooks,
+                                                                uint8_t *__restrict__ codes, int64_t code_stride_bh,
+                                                                int B, int H, int64_t N, int d_k, int m)
+{
+    __shared__ double x_s[kEncFewKeys][DSUB];
+    __shared__ uint64_t red_k[kEncFewKeys][kCentroids / kWave];
+    __shared__ int red_c[kEncFewKeys][kCentroids / kWave];
+
+    const int i = blockIdx.y;
+    const int h = blockIdx.z;
+    const int c = threadIdx.x;
+    const int lane = c & (kWave - 1), wave = c / kWave;
+    const int64_t r0 = (int64_t)blockIdx.x * kEncFewKeys;   // first flat (b, n) of the block
+    const int64_t rows = (int64_t)B * N;
+
+    for (int e = threadIdx.x; e < kEncFewKeys * DSUB; e += kCentroids) {
+        const int64_t r = r0 + e / DSUB;
+        double v = 0.0;
+        if (r < rows) {
+            const int64_t b = r / N, n = r % N;
+            v = widen<KT>(keys[((b * H + h) * N + n) * d_k + (int64_t)i * DSUB + e % DSUB]);
+        }
+        x_s[e / DSUB][e % DSUB] = v;
+    }
+    double y[DSUB];
+    {
+        const float *src = codebooks + (((int64_t)h * m + i) * kCentroids + c) * DSUB;
+#pragma unroll
+        for (int j = 0; j < DSUB; ++j)
+            y[j] = (double)src[j];
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int k = 0; k < kEncFewKeys; ++k) {
+        double acc = 0.0;
+#pragma unroll
+        for (int j = 0; j < DSUB; ++j) {
+            double diff = x_s[k][j] - y[j];
+            double sq = diff * diff;
+            acc = acc + sq;
+        }
+        uint64_t key = dist_order_key(acc, c);
+        int best = c;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint64_t k2 = __shfl_xor((unsigned long long)key, off);
+            const int c2 = __shfl_xor(best, off);
+            argmin_merge(key, best, k2, c2);
+        }
+        if (lane == 0) {
+            red_k[k][wave] = key;
+            red_c[k][wave] = best;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < kEncFewKeys) {
+        const int k = threadIdx.x;
+        const int64_t r = r0 + k;
+        if (r < rows) {
+            uint64_t key = red_k[k][0];
+            int best = red_c[k][0];
+#pragma unroll
+            for (int w = 1; w < kCentroids / kWave; ++w)
+                argmin_merge(key, best, red_k[k][w], red_c[k][w]);
+            const int64_t b = r / N, n = r % N;
+            codes[(b * H + h) * code_stride_bh + n * m + i] = (uint8_t)best;
+        }
+    }
+}
+
+template <typename KT>
+static bool launch_encode_few(const lookat_shape *s, int64_t N, const void *keys, const float *codebooks,
+                              uint8_t *codes, int64_t code_stride_bh, hipStream_t st)
+{
+    const int d_sub = s->d_k / s->m;
+    const int64_t rows = (int64_t)s->B * N;
+    dim3 grid((unsigned)((rows + kEncFewKeys - 1) / kEncFewKeys), (unsigned)s->m, (unsigned)s->H);
+    dim3 block(kCentroids);
+    const KT *k = static_cast<const KT *>(keys);
+#define LOOKAT_ENCF_CASE(D)                                                                                     \
+    case D:                                                                                                     \
+        hipLaunchKernelGGL((encode_few_kernel<KT, D>), grid, block, 0, st, k, codebooks, codes, code_stride_bh, \
+                           s->B, s->H, N, s->d_k, s->m);                                                        \
+        return true;
+    switch (d_sub) {
+        LOOKAT_ENCF_CASE(1)
+        LOOKAT_ENCF_CASE(2)
+        LOOKAT_ENCF_CASE(4)
+        LOOKAT_ENCF_CASE(8)
+        LOOKAT_ENCF_CASE(16)
+        LOOKAT_ENCF_CASE(32)
+    default:
+        return false;   // no centroid-parallel variant for this sub-vector length
+    }
+#undef LOOKAT_ENCF_CASE
+}
+
 template <typename KT>
 static void launch_encode(const lookat_shape *s, int64_t N, const void *keys, const float *codebooks, uint8_t *codes,
                           int64_t code_stride_bh, hipStream_t st)
@@ -169,9 +296,21 @@ extern "C" int lookat_encode_keys(const lookat_shape *shape, int64_t N, const vo
     if ((rows + kEncThreads - 1) / kEncThreads > 0x7fffffffLL || shape->H > 65535 || shape->m > 65535)
         return fail(LOOKAT_ERR_UNSUPPORTED, "B*N=%lld keys per head exceed one launch", (long long)rows);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (key_dtype == LOOKAT_F16)
-        launch_encode<__half>(shape, N, keys, codebooks, codes, code_stride_bh, st);
-    else
-        launch_encode<float>(shape, N, keys, codebooks, codes, code_stride_bh, st);
+    // Few keys per head (a decode step appends one per sequence): spread the centroids over
+    // the threads.  Many keys (prefill): one thread per key.  The crossover is where the
+    // thread-per-key grid reaches a few workgroups per compute unit.
+    const int64_t per_key_blocks = (rows + kEncThreads - 1) / kEncThreads * shape->m * shape->H;
+    bool done = false;
+    if (per_key_blocks < 1024 && (rows + kEncFewKeys - 1) / kEncFewKeys <= 0x7fffffffLL) {
+        done = (key_dtype == LOOKAT_F16)
+                   ? launch_encode_few<__half>(shape, N, keys, codebooks, codes, code_stride_bh, st)
+                   : launch_encode_few<float>(shape, N, keys, codebooks, codes, code_stride_bh, st);
+    }
+    if (!done) {
+        if (key_dtype == LOOKAT_F16)
+            launch_encode<__half>(shape, N, keys, codebooks, codes, code_stride_bh, st);
+        else
+            launch_encode<float>(shape, N, keys, codebooks, codes, code_stride_bh, st);
+    }
     return check_launch("lookat_encode_keys");
 }

@@ -7,7 +7,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "lookat.h")
+HEADERS = [os.path.join(ROOT, "include", f) for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if f.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,14 +21,17 @@ def lib():
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lookat_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(lookat_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode"} <= set(names)
+    assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
+            "lookat_probe_stream_read"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -102,3 +106,17 @@ def test_binding_refuses_host_tensors():
     cb = torch.zeros((1, 4, 256, 16))
     with pytest.raises(ValueError):
         binding.lookat_encode_keys(torch.zeros((1, 1, 4, 64)), cb)
+
+
+def test_kmeans_and_probe_argument_errors(lib):
+    s = Shape(2, 3, 64, 4, 256)
+    f = lib.lookat_kmeans_step
+    assert f(ctypes.byref(s), 10, FAKE, FAKE, FAKE + 0x1000, FAKE, None) == E_SHAPE      # B must be 1
+    s1 = Shape(1, 3, 64, 4, 256)
+    assert f(ctypes.byref(s1), 0, FAKE, FAKE, FAKE + 0x1000, FAKE, None) == E_SHAPE
+    assert f(ctypes.byref(s1), 10, FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE              # in == out
+    assert f(ctypes.byref(s1), 10, None, FAKE, FAKE + 0x1000, FAKE, None) == E_NULL
+    p = lib.lookat_probe_stream_read
+    assert p(None, 1024, FAKE, None) == E_NULL
+    assert p(FAKE, 1000, FAKE, None) == E_SHAPE
+    assert p(FAKE + 8, 1024, FAKE, None) == E_ALIGN

@@ -67,7 +67,35 @@ def test_encode_bit_exact(lk, d_k, m, key_dtype):
     assert np.array_equal(got, ref), f"{(got != ref).sum()} of {ref.size} codes differ"
 
 
-def test_encode_ties_and_duplicates(lk):
+@pytest.mark.parametrize("d_k,m,key_dtype", [(64, 4, "float32"), (128, 16, "float16"), (64, 2, "float16")])
+def test_encode_bit_exact_many_keys(lk, d_k, m, key_dtype):
+    """Enough keys per head that the one-thread-per-key kernel runs (the small cases above take
+    the centroid-parallel kernel); ragged last block."""
+    cfg = li.shrink(li.CONFIGS["C2"], B=4, H=4, L=4096 + 37, d_k=d_k, m=m, n_calib=512, key_dtype=key_dtype)
+    case = li.make_case(cfg, seed=1500 + d_k + m)
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 1)
+    ref = oracle.encode_keys(case["keys"], cb)
+    got = lk.lookat_encode_keys(dev(case["keys"]), dev(cb)).cpu().numpy()
+    assert np.array_equal(got, ref), f"{(got != ref).sum()} of {ref.size} codes differ"
+
+
+@pytest.mark.parametrize("N", [3, 5000])
+def test_encode_nan_distances(lk, N):
+    """A NaN distance never wins, unless it is centroid 0's (the scan starts there)."""
+    rng = np.random.default_rng(6)
+    cb = rng.standard_normal((2, 4, 256, 16)).astype(np.float32)
+    cb[0, 0, 0, 3] = np.nan          # head 0, subspace 0: centroid 0 is NaN -> code 0 for every key
+    cb[0, 1, 77, 0] = np.nan         # a NaN centroid elsewhere is never chosen
+    cb[1, 2, 255] = np.nan
+    keys = rng.standard_normal((2, 2, N, 64)).astype(np.float32)
+    ref = oracle.encode_keys(keys, cb)
+    got = lk.lookat_encode_keys(dev(keys), dev(cb)).cpu().numpy()
+    assert np.array_equal(got, ref)
+    assert (got[:, 0, :, 0] == 0).all() and not (got[:, 0, :, 1] == 77).any() and not (got[:, 1, :, 2] == 255).any()
+
+
+@pytest.mark.parametrize("n_keys", [70, 9000])
+def test_encode_ties_and_duplicates(lk, n_keys):
     d_sub, K = 16, 256
     rng = np.random.default_rng(4)
     cb = (rng.standard_normal((2, 4, K, d_sub)) * 3).astype(np.float32)
@@ -75,7 +103,7 @@ def test_encode_ties_and_duplicates(lk):
     cb[0, 0, 100] = 0.0
     cb[0, 0, 200] = 2.0                     # keys of all-ones are exactly midway between 100 and 200
     cb[1] = 1.5                             # a head whose centroids are all equal -> code 0 everywhere
-    keys = rng.standard_normal((2, 2, 70, 64)).astype(np.float32)
+    keys = rng.standard_normal((2, 2, n_keys, 64)).astype(np.float32)
     keys[:, 0, :10, :16] = 1.0
     keys[:, 0, 10:20, 16:32] = cb[0, 1, 5]  # exactly on the duplicated centroid
     ref = oracle.encode_keys(keys, cb)
@@ -238,3 +266,36 @@ def test_config_c3_reduced_whole_path(lk):
     cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 1)
     _check_pipeline(lk, case, cb, splits=0)
     _check_pipeline(lk, case, cb, splits=5)
+
+
+# ---------------------------------------------------------------- codebook learning ----
+
+@pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (128, 16), (24, 2)])
+def test_kmeans_step_bit_exact(lk, d_k, m):
+    """Assignment = the encoder (bit-exact); the update is an fp64 sum in key order, so the new
+    codebooks must equal the oracle's exactly, iteration after iteration."""
+    cfg = li.shrink(li.CONFIGS["C1"], H=3, L=8, d_k=d_k, m=m, n_calib=1500, rank=min(8, d_k))
+    case = li.make_case(cfg, seed=4000 + d_k + m)
+    calib, cb = case["calib"], case["cb_init"]
+    cb_gpu = dev(cb)
+    for it in range(3):
+        ref, _ = oracle.kmeans_step(calib, cb)
+        got, assign = lk.lookat_kmeans_step(dev(calib), cb_gpu)
+        assert np.array_equal(assign.cpu().numpy(), oracle.encode_keys(calib[None], cb)[0])
+        assert np.array_equal(got.cpu().numpy(), ref), f"iteration {it}"
+        cb, cb_gpu = ref, got
+    # the multi-iteration helper lands on the same codebooks
+    again = lk.lookat_kmeans(dev(calib), dev(case["cb_init"]), 3).cpu().numpy()
+    assert np.array_equal(again, cb)
+
+
+def test_kmeans_empty_cluster_keeps_centroid(lk):
+    cfg = li.shrink(li.CONFIGS["C1"], H=1, L=8, n_calib=300, m=2)
+    case = li.make_case(cfg, seed=4100)
+    cb = case["cb_init"].copy()
+    cb[0, 0, 17] = 1e6          # no calibration key is anywhere near: cluster 17 stays empty
+    ref, _ = oracle.kmeans_step(case["calib"], cb)
+    got, _ = lk.lookat_kmeans_step(dev(case["calib"]), dev(cb))
+    got = got.cpu().numpy()
+    assert np.array_equal(got, ref)
+    assert np.array_equal(got[0, 0, 17], cb[0, 0, 17])

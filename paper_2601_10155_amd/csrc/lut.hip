@@ -88,6 +88,120 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_generic_kernel(const QT
     }
 }
 
+// ---- many queries per head: the table build is a dense contraction -> matrix cores ------
+// Per (head h, subspace i):  LUT[r][c] = sum_j Q[r][j] * C[c][j]  with r over the B*T queries
+// of the head, c over the 256 centroids, j over d_sub: an [R x d_sub] . [d_sub x 256] product.
+// One wavefront owns 32-query tiles and keeps the whole [d_sub x 256] codebook slice in
+// registers as MFMA B-fragments; per tile it issues 8 column blocks x d_sub/2 steps of
+// v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate: same accuracy class as the vector kernel)
+// and streams the 32 x 256 fp32 results out, each store instruction writing two full 128-byte
+// rows segments.  The kernel is bound by that output stream (d_sub*2 flops per 4 bytes
+// written), not by the matrix cores.
+//   fragment layout of the 32x32x2 MFMA: A[row = lane%32][k = lane/32], B[k = lane/32][col = lane%32],
+//   D[row = 8*(r/4) + 4*(lane/32) + r%4][col = lane%32] for accumulator register r = 0..15.
+typedef float v16f __attribute__((ext_vector_type(16)));
+constexpr int kMfmaWaves = 4;
+
+template <typename QT, int DSUB>
+__global__ __launch_bounds__(kMfmaWaves *kWave) void build_lut_mfma_kernel(const QT *__restrict__ q,
+                                                                           const float *__restrict__ codebooks,
+                                                                           float *__restrict__ lut, int B, int H,
+                                                                           int T, int d_k, int m, int tiles_per_wave)
+{
+    constexpr int KS = DSUB / 2;
+    const int i = blockIdx.y;
+    const int h = blockIdx.z;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int n = lane & 31;
+    const int kh = lane >> 5;
+    const int64_t nq = (int64_t)B * T;
+    const int64_t ntiles = (nq + 31) / 32;
+
+    float bfrag[8][KS];
+    {
+        const float *cb = codebooks + ((int64_t)h * m + i) * kCentroids * DSUB;
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                bfrag[nt][s] = cb[(nt * 32 + n) * DSUB + 2 * s + kh];
+    }
+
+    int64_t tile = ((int64_t)blockIdx.x * kMfmaWaves + wave) * tiles_per_wave;
+    for (int it = 0; it < tiles_per_wave && tile < ntiles; ++it, ++tile) {
+        float afrag[KS];
+        {
+            const int64_t r = tile * 32 + n;
+            const bool live = r < nq;
+            const int64_t b = live ? r / T : 0, t = live ? r % T : 0;
+            const QT *src = q + ((b * H + h) * T + t) * d_k + (int64_t)i * DSUB + kh;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                afrag[s] = live ? to_f32<QT>(src[2 * s]) : 0.f;
+        }
+        // output row offsets of the 16 accumulator registers of this lane
+        int64_t row_off[16];
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) {
+            const int64_t r = tile * 32 + 8 * (rr / 4) + 4 * kh + (rr % 4);
+            if (r < nq) {
+                const int64_t b = r / T, t = r % T;
+                row_off[rr] = ((((b * H + h) * T + t) * m) + i) * kCentroids + n;
+            } else {
+                row_off[rr] = -1;
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            v16f acc;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr)
+                acc[rr] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag[s], bfrag[nt][s], acc, 0, 0, 0);
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr)
+                if (row_off[rr] >= 0)
+                    lut[row_off[rr] + nt * 32] = acc[rr];
+        }
+    }
+}
+
+template <typename QT>
+static bool launch_build_lut_mfma(const lookat_shape *s, int T, const void *q, const float *codebooks, float *lut,
+                                  hipStream_t st)
+{
+    const int d_sub = s->d_k / s->m;
+    const int64_t nq = (int64_t)s->B * T;
+    const int64_t ntiles = (nq + 31) / 32;
+    // tiles per wave: reuse the codebook fragments, but keep a few thousand workgroups
+    int tpw = 1;
+    while (tpw < 16 && (ntiles / (kMfmaWaves * tpw * 2)) * s->m * s->H >= 2048)
+        tpw *= 2;
+    const int64_t gx = (ntiles + (int64_t)kMfmaWaves * tpw - 1) / ((int64_t)kMfmaWaves * tpw);
+    if (gx > 0x7fffffffLL)
+        return false;
+    dim3 grid((unsigned)gx, (unsigned)s->m, (unsigned)s->H);
+    dim3 block(kMfmaWaves * kWave);
+    const QT *qp = static_cast<const QT *>(q);
+#define LOOKAT_LUTM_CASE(D)                                                                                       \
+    case D:                                                                                                       \
+        hipLaunchKernelGGL((build_lut_mfma_kernel<QT, D>), grid, block, 0, st, qp, codebooks, lut, s->B, s->H, T, \
+                           s->d_k, s->m, tpw);                                                                    \
+        return true;
+    switch (d_sub) {
+        LOOKAT_LUTM_CASE(2)
+        LOOKAT_LUTM_CASE(4)
+        LOOKAT_LUTM_CASE(8)
+        LOOKAT_LUTM_CASE(16)
+    default:
+        return false;   // fragments would not fit the register file: vector kernel
+    }
+#undef LOOKAT_LUTM_CASE
+}
+
 template <typename QT>
 static void launch_build_lut(const lookat_shape *s, int T, const void *q, const float *codebooks, float *lut,
                              hipStream_t st)
@@ -142,9 +256,18 @@ extern "C" int lookat_build_lut(const lookat_shape *shape, int32_t T, const void
     if ((int64_t)shape->B * T > 0x7fffffffLL || shape->H > 65535)
         return fail(LOOKAT_ERR_UNSUPPORTED, "B*T or H too large for one launch");
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (q_dtype == LOOKAT_F16)
-        launch_build_lut<__half>(shape, T, q, codebooks, lut, st);
-    else
-        launch_build_lut<float>(shape, T, q, codebooks, lut, st);
+    // From 256 queries per head on, the build is a dense [B*T x d_sub].[d_sub x 256] contraction
+    // per (head, subspace) and runs on the matrix cores; below that the 32-row MFMA tiles would be
+    // mostly padding and the vector kernel is used.
+    bool done = false;
+    if ((int64_t)shape->B * T >= 256)
+        done = (q_dtype == LOOKAT_F16) ? launch_build_lut_mfma<__half>(shape, T, q, codebooks, lut, st)
+                                       : launch_build_lut_mfma<float>(shape, T, q, codebooks, lut, st);
+    if (!done) {
+        if (q_dtype == LOOKAT_F16)
+            launch_build_lut<__half>(shape, T, q, codebooks, lut, st);
+        else
+            launch_build_lut<float>(shape, T, q, codebooks, lut, st);
+    }
     return check_launch("lookat_build_lut");
 }

@@ -145,6 +145,20 @@ def test_build_lut_parity(lk, d_k, m, q_dtype, B, T):
     assert_lut_close(got, case["q"], cb, ref)
 
 
+@pytest.mark.parametrize("d_k,m", [(128, 16), (64, 4), (64, 16), (128, 32), (64, 32)])
+@pytest.mark.parametrize("q_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("B,T", [(1, 256), (3, 333), (2, 1031)])
+def test_build_lut_batched_matrix_core_path(lk, d_k, m, q_dtype, B, T):
+    """>= 256 queries per head: the MFMA kernel (d_sub in {2,4,8,16}); ragged 32-query tiles and
+    tiles that straddle batch entries."""
+    cfg = li.shrink(li.CONFIGS["C4"], B=B, H=2, L=4, T=T, d_k=d_k, m=m, n_calib=300, q_dtype=q_dtype)
+    case = li.make_case(cfg, seed=2500 + d_k + m + T)
+    cb = case["cb_init"]
+    ref = oracle.build_lut(case["q"], cb)
+    got = lk.lookat_build_lut(dev(case["q"]), dev(cb)).cpu().numpy()
+    assert_lut_close(got, case["q"], cb, ref)
+
+
 # ---------------------------------------------------------------- decode ---------------
 
 def _decode_case(rng, B, H, L, d_k, m, lut_scale=2.0):

@@ -143,7 +143,8 @@ def attend_decode(lut, codes, values, scale, want_scores=False, want_alpha=False
 
 
 def score_prefill(lut, codes):
-    """lut [B,H,T,m,K], codes [B,H,L,m] -> causal scores [B,H,T,L] fp32, -inf where l > t."""
+    """lut [B,H,T,m,K], codes [B,H,L,m], L >= T -> causal scores [B,H,T,L] fp32; the queries are
+    the last T positions, entries with l > t + (L - T) are -inf."""
     lut = np.ascontiguousarray(lut, dtype=np.float32)
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     B, H, T, m, K = lut.shape

@@ -235,20 +235,24 @@ int oracle_attend_decode(int B, int H, int64_t L, int d_k, int m, int K,
     return rc;
 }
 
-/* Prefill form of the lookup-and-sum: T = L queries of one block, query t scores
- * the keys l <= t of the same block (causal, self included); entries with l > t are
+/* Prefill form of the lookup-and-sum: the T queries of a block are the last T positions
+ * of a cache of L >= T keys, so query t sits at position t + (L - T) and scores the keys
+ * l <= t + (L - T) (causal, self included; for L == T: l <= t).  Entries it may not see are
  * written as -inf.  lut is [B,H,T,m,K]; scores [B,H,T,L] fp32 unscaled. */
 int oracle_score_prefill(int B, int H, int T, int64_t L, int m, int K,
                          const float *lut, const uint8_t *codes, float *scores)
 {
     int64_t BH = (int64_t)B * H;
+    if (L < T)
+        return -2;
+    const int64_t off = L - T;
 #pragma omp parallel for schedule(static)
     for (int64_t bh = 0; bh < BH; ++bh) {
         for (int t = 0; t < T; ++t) {
             const float *tab = lut + (bh * T + t) * m * K;
             for (int64_t l = 0; l < L; ++l) {
                 float v;
-                if (l <= t)
+                if (l <= t + off)
                     v = (float)adc_score(tab, codes + (bh * L + l) * m, m, K);
                 else
                     v = -INFINITY;

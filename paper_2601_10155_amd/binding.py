@@ -54,6 +54,8 @@ def load_library():
         lib.lookat_attend_decode_auto_splits.restype = i32
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
+        lib.lookat_score_prefill.restype = ctypes.c_int
         lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
         lib.lookat_kmeans_step.restype = ctypes.c_int
         lib.lookat_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -211,6 +213,32 @@ def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.T
                                     out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
                                     _stream(values)))
     return out
+
+
+def lookat_score_prefill(q: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
+                         scores_out: torch.Tensor | None = None) -> torch.Tensor:
+    """q [B,H,T,d_k] fp16|fp32, codes [B,H,L,m] u8 (L >= T) -> causal scores [B,H,T,L] fp32
+    (-inf where key l is later than query t's position t + L - T)."""
+    lib = load_library()
+    q = _dev(q, "q").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    _dev(codes, "codes")
+    B, H, T, d_k = q.shape
+    Hc, m, K, d_sub = cb.shape
+    L = codes.shape[2]
+    if Hc != H or m * d_sub != d_k or cb.dtype != torch.float32:
+        raise ValueError("codebooks must be fp32 [H,m,K,d_k/m]")
+    if codes.dtype != torch.uint8 or codes.shape[:2] != (B, H) or codes.shape[3] != m:
+        raise ValueError("codes must be uint8 [B,H,L,m]")
+    cs = _bh_stride(codes, "codes")
+    if scores_out is None:
+        scores_out = torch.empty((B, H, T, L), dtype=torch.float32, device=q.device)
+    if scores_out.dtype != torch.float32 or scores_out.numel() != B * H * T * L or not scores_out.is_contiguous():
+        raise ValueError("scores_out must be contiguous fp32 [B,H,T,L]")
+    shape = _Shape(B, H, d_k, m, K)
+    _check(lib.lookat_score_prefill(ctypes.byref(shape), T, L, q.data_ptr(), _dtype_tag(q), cb.data_ptr(),
+                                    codes.data_ptr(), cs, scores_out.data_ptr(), _stream(q)))
+    return scores_out
 
 
 def lookat_kmeans_step(calib: torch.Tensor, codebooks: torch.Tensor, codebooks_out: torch.Tensor | None = None,

@@ -31,7 +31,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
-            "lookat_probe_stream_read"} <= set(names)
+            "lookat_probe_stream_read", "lookat_score_prefill"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -120,3 +120,24 @@ def test_kmeans_and_probe_argument_errors(lib):
     assert p(None, 1024, FAKE, None) == E_NULL
     assert p(FAKE, 1000, FAKE, None) == E_SHAPE
     assert p(FAKE + 8, 1024, FAKE, None) == E_ALIGN
+
+
+def test_score_prefill_argument_errors(lib):
+    s = Shape(2, 3, 128, 16, 256)
+    f = lib.lookat_score_prefill
+    ok_args = [ctypes.byref(s), 64, 64, FAKE, 1, FAKE, FAKE, 64 * 16, FAKE, None]
+    def call(**kw):
+        a = list(ok_args)
+        for k, v in kw.items():
+            a[{"T": 1, "L": 2, "q": 3, "dt": 4, "cb": 5, "codes": 6, "cs": 7, "scores": 8}[k]] = v
+        return f(*a)
+    assert call(T=0) == E_SHAPE
+    assert call(L=63) == E_SHAPE                 # fewer keys than queries
+    assert call(dt=9) == E_DTYPE
+    assert call(codes=None) == E_NULL
+    assert call(cs=64 * 16 - 16) == E_SHAPE
+    assert call(q=FAKE + 2) == E_ALIGN
+    assert call(codes=FAKE + 8) == E_ALIGN
+    bad = Shape(2, 3, 96, 4, 256)
+    a = list(ok_args); a[0] = ctypes.byref(bad); a[7] = 64 * 4
+    assert f(*a) == E_UNSUP

@@ -313,3 +313,55 @@ def test_kmeans_empty_cluster_keeps_centroid(lk):
     got = got.cpu().numpy()
     assert np.array_equal(got, ref)
     assert np.array_equal(got[0, 0, 17], cb[0, 0, 17])
+
+
+# ---------------------------------------------------------------- causal prefill scoring ----
+
+def _prefill_check(lk, case, cb, codes):
+    q = case["q"]
+    lut_ref = oracle.build_lut(q, cb)
+    ref = oracle.score_prefill(lut_ref, codes)
+    got = lk.lookat_score_prefill(dev(q), dev(cb), dev(codes)).cpu().numpy()
+    assert got.shape == ref.shape
+    vis = np.isfinite(ref)
+    assert np.array_equal(np.isneginf(got), ~vis), "mask differs"
+    B, H, T, m, K = lut_ref.shape
+    L = codes.shape[2]
+    # tolerance relative to sum_i |LUT_i[c_i]| per (t, l)
+    mag = np.zeros((B, H, T, L))
+    for i in range(m):
+        tab = np.abs(lut_ref[:, :, :, i, :].astype(np.float64))                      # [B,H,T,K]
+        idx = np.broadcast_to(codes[:, :, None, :, i].astype(np.int64), (B, H, T, L))
+        mag += np.take_along_axis(tab, idx, axis=-1)
+    err = np.abs(got[vis].astype(np.float64) - ref[vis].astype(np.float64))
+    assert np.all(err <= REL * np.maximum(mag[vis], 1e-6)), f"max err {err.max()}"
+
+
+@pytest.mark.parametrize("d_k,m", [(128, 16), (128, 8), (64, 4), (64, 2), (64, 16)])
+@pytest.mark.parametrize("q_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0)])
+def test_score_prefill_parity(lk, d_k, m, q_dtype, T, extra):
+    """Ragged query tiles (T not a multiple of 8 or 32), queries that are the tail of a longer
+    cache (extra > 0), a single query."""
+    L = T + extra
+    cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)
+    case = li.make_case(cfg, seed=5000 + d_k + m + T)
+    cb = case["cb_init"]
+    codes = oracle.encode_keys(case["keys"], cb)
+    _prefill_check(lk, case, cb, codes)
+
+
+def test_score_prefill_matches_decode_rows(lk):
+    """Row t of the causal block equals the decode scores of query t over the first t+1 keys."""
+    cfg = li.shrink(li.CONFIGS["C4"], B=1, H=2, L=200, T=200, n_calib=400)
+    case = li.make_case(cfg, seed=5100)
+    cb = case["cb_init"]
+    codes = lk.lookat_encode_keys(dev(case["keys"]), dev(cb))
+    block = lk.lookat_score_prefill(dev(case["q"]), dev(cb), codes).cpu().numpy()
+    lut = lk.lookat_build_lut(dev(case["q"]), dev(cb))
+    for t in (0, 7, 8, 131, 199):
+        s = torch.empty((1, 2, t + 1), dtype=torch.float32, device="cuda")
+        lk.lookat_attend_decode(lut[:, :, t].contiguous(), codes[:, :, :t + 1], dev(case["values"])[:, :, :t + 1],
+                                0.1, scores_out=s)
+        d = np.abs(block[:, :, t, :t + 1] - s.cpu().numpy())
+        assert d.max() <= 1e-5

@@ -282,6 +282,21 @@ def test_score_prefill_matches_numpy_gather():
                 else:
                     ref = sum(float(lut[0, h, t, i, codes[0, h, l, i]]) for i in range(m))
                     assert abs(s[0, h, t, l] - ref) <= 1e-6
+    # queries that are the last T positions of a longer cache: query t sees l <= t + (L - T)
+    L = T + 5
+    codes2 = rng.integers(0, 256, size=(B, H, L, m), dtype=np.uint8)
+    s2 = oracle.score_prefill(lut, codes2)
+    assert s2.shape == (B, H, T, L)
+    for h in range(H):
+        for t in range(T):
+            for l in range(L):
+                if l > t + 5:
+                    assert s2[0, h, t, l] == -np.inf
+                else:
+                    ref = sum(float(lut[0, h, t, i, codes2[0, h, l, i]]) for i in range(m))
+                    assert abs(s2[0, h, t, l] - ref) <= 1e-6
+    with pytest.raises(RuntimeError):
+        oracle.score_prefill(lut, codes2[:, :, :T - 1])
     # row t of the causal scores equals decode scores of query t restricted to l <= t
     dec = oracle.adc_scores(lut[:, :, 5], codes)
     assert np.array_equal(dec[..., :6], s[:, :, 5, :6])

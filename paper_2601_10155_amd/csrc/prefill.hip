@@ -5,23 +5,27 @@
 //     scores[b,h,t,l] = sum_i LUT_{b,h,t,i}[codes[b,h,l,i]]   for l <= t + (L - T),  else -inf.
 //
 // Shape of the computation on gfx950
-//   * one workgroup (1024 threads) = one (b,h) and kGroup consecutive tiles of TQ queries;
-//   * the tables of a tile live in LDS as lut_s[i][c][TQ] (fp32): the TQ queries' entries of one
-//     (subspace, centroid) are adjacent, so ONE 16-byte LDS read returns four queries' entries
-//     for a key's code.  Compared with a [query][i][c] layout and 4-byte gathers this needs a
-//     quarter of the LDS instructions and meets fewer bank conflicts (8 lanes x 16 bytes per
-//     pass instead of 32 lanes x 4 bytes at random banks);
-//   * the tile's tables are computed on the vector ALU from codebook rows kept in registers
-//     for the whole workgroup (with TQ = 8 the contraction is 8 wide: a 32x32 or 16x16 MFMA
-//     tile would be 50-75% padding, and this step is a few percent of the kernel);
-//   * the scoring loop is bound by LDS read bandwidth (m * TQ * 4 bytes per key and tile) and
-//     by the scores written (4 bytes per (query, key)).
+//   * one workgroup (512 threads) = one (b,h) and kPfGroup consecutive tiles of TQ = 4 queries;
+//     two workgroups fit a compute unit (64 KB of tables each), so one builds tables on the
+//     vector ALU while the other gathers from LDS;
+//   * the tables of a tile live in LDS as lut_s[i][c][4] (fp32): the four queries' entries of one
+//     (subspace, centroid) are adjacent, so ONE 16-byte LDS read per (key, subspace) serves four
+//     queries.  Against a [query][i][c] layout with 4-byte gathers this is a quarter of the LDS
+//     instructions, and the 16-byte stride spreads a pass of 8 lanes over all banks;
+//   * the head's codebook is held in registers across the workgroup's tiles (thread p owns the
+//     (subspace, centroid) pairs p, p+512, ...), so a tile's tables cost d_sub FMAs per entry and
+//     no codebook traffic.  With 4 queries per tile the contraction is 4 wide: a 32x32 or 16x16
+//     MFMA tile would be 75-87% padding and fp32 MFMA has no rate advantage over the vector
+//     ALU, so this step stays on the vector ALU;
+//   * the scoring loop is bound by LDS read bandwidth (4 bytes per (query, key, subspace)) and by
+//     the scores written (4 bytes per (query, key)).
 #include "common.h"
 
 namespace lookat {
 
-constexpr int kPfThreads = 1024;
-constexpr int kPfGroup = 4;   // query tiles per workgroup (codebook registers reused)
+constexpr int kPfThreads = 512;
+constexpr int kPfTQ = 4;      // queries per tile
+constexpr int kPfGroup = 8;   // query tiles per workgroup (codebook registers reused)
 
 typedef unsigned int pf_v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int pf_v2u __attribute__((ext_vector_type(2)));
@@ -42,16 +46,42 @@ struct PrefillArgs {
     int64_t L;
     int T;
     int H;
-    int tiles;                // ceil(T / TQ)
+    int tiles;                // ceil(T / 4)
+};
+
+template <int M>
+struct PfCodes {
+    uint32_t w[(M + 3) / 4];
+    __device__ __forceinline__ void load(const uint8_t *cp)
+    {
+        if constexpr (M == 2) {
+            w[0] = *reinterpret_cast<const uint16_t *>(cp);
+        } else if constexpr (M == 4) {
+            w[0] = *reinterpret_cast<const uint32_t *>(cp);
+        } else if constexpr (M == 8) {
+            const pf_v2u t = *reinterpret_cast<const pf_v2u *>(cp);
+            w[0] = t.x;
+            w[1] = t.y;
+        } else {
+            const pf_v4u t = *reinterpret_cast<const pf_v4u *>(cp);
+            w[0] = t.x;
+            w[1] = t.y;
+            w[2] = t.z;
+            w[3] = t.w;
+        }
+    }
+    __device__ __forceinline__ uint32_t byte(int i) const { return (w[i / 4] >> (8 * (i % 4))) & 0xffu; }
 };
 
 // grid = (ceil(tiles / kPfGroup), BH); heavy (late) tiles are dispatched first.
-template <typename QT, int DK, int M, int TQ>
-__global__ __launch_bounds__(kPfThreads) void score_prefill_kernel(const PrefillArgs a)
+template <typename QT, int DK, int M>
+__global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const PrefillArgs a)
 {
+    constexpr int TQ = kPfTQ;
     constexpr int DSUB = DK / M;
     constexpr int PAIRS = M * kCentroids;                          // (subspace, centroid) pairs
     constexpr int PP = (PAIRS + kPfThreads - 1) / kPfThreads;      // pairs per thread
+    constexpr int GB = M < 4 ? M : 4;                              // gathers in flight per key
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                      // [M][256][TQ]
     float *q_s = smem + PAIRS * TQ;           // [TQ][DK]
@@ -70,10 +100,15 @@ __global__ __launch_bounds__(kPfThreads) void score_prefill_kernel(const Prefill
     for (int k = 0; k < PP; ++k) {
         const int p = tid + k * kPfThreads;
         if (p < PAIRS) {
-            const float *src = a.codebooks + ((int64_t)h * PAIRS + p) * DSUB;
+            const float4 *src = reinterpret_cast<const float4 *>(a.codebooks + ((int64_t)h * PAIRS + p) * DSUB);
 #pragma unroll
-            for (int j = 0; j < DSUB; ++j)
-                row[k][j] = src[j];
+            for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+                const float4 v = src[j4];
+                row[k][4 * j4] = v.x;
+                row[k][4 * j4 + 1] = v.y;
+                row[k][4 * j4 + 2] = v.z;
+                row[k][4 * j4 + 3] = v.w;
+            }
         }
     }
 
@@ -83,77 +118,71 @@ __global__ __launch_bounds__(kPfThreads) void score_prefill_kernel(const Prefill
         if (tile >= a.tiles)
             continue;
         const int t0 = tile * TQ;
-        __syncthreads();   // previous tile's readers are done with lut_s / q_s
+        const int64_t vis_last = t0 + TQ - 1 + off;                     // last key any query of the tile sees
+        const int64_t kmax = (vis_last + 1 < a.L) ? vis_last + 1 : a.L;
+
+        __syncthreads();   // the previous tile's readers are done with lut_s / q_s
         for (int e = tid; e < TQ * DK; e += kPfThreads) {
             const int t = t0 + e / DK;
             q_s[e] = (t < a.T) ? pf_to_f32<QT>(qg[(int64_t)t * DK + e % DK]) : 0.f;
         }
+        // codes of this thread's first key: requested now, needed after the table build
+        PfCodes<M> kc;
+        if (tid < kmax)
+            kc.load(codes_bh + (int64_t)tid * M);
         __syncthreads();
-        // ---- tables of the tile: lut_s[(i*256 + c)*TQ + t] = q[t]^(i) . C_i[c], j ascending ----
+
+        // ---- tables of the tile: lut_s[(i*256 + c)*4 + t] = q[t]^(i) . C_i[c], j ascending ----
 #pragma unroll
         for (int k = 0; k < PP; ++k) {
             const int p = tid + k * kPfThreads;
             if (p < PAIRS) {
-                const int i = p / kCentroids;
+                const int i = p / kCentroids;   // uniform over the wavefront: q_s reads are broadcasts
                 float acc[TQ];
 #pragma unroll
                 for (int t = 0; t < TQ; ++t) {
+                    const float4 *qv = reinterpret_cast<const float4 *>(q_s + t * DK + i * DSUB);
                     acc[t] = 0.f;
 #pragma unroll
-                    for (int j = 0; j < DSUB; ++j)
-                        acc[t] = fmaf(q_s[t * DK + i * DSUB + j], row[k][j], acc[t]);
+                    for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+                        const float4 x = qv[j4];
+                        acc[t] = fmaf(x.x, row[k][4 * j4], acc[t]);
+                        acc[t] = fmaf(x.y, row[k][4 * j4 + 1], acc[t]);
+                        acc[t] = fmaf(x.z, row[k][4 * j4 + 2], acc[t]);
+                        acc[t] = fmaf(x.w, row[k][4 * j4 + 3], acc[t]);
+                    }
                 }
-                float4 *dst = reinterpret_cast<float4 *>(lut_s + (int64_t)p * TQ);
-#pragma unroll
-                for (int t4 = 0; t4 < TQ / 4; ++t4)
-                    dst[t4] = make_float4(acc[4 * t4], acc[4 * t4 + 1], acc[4 * t4 + 2], acc[4 * t4 + 3]);
+                *reinterpret_cast<float4 *>(lut_s + (int64_t)p * TQ) = make_float4(acc[0], acc[1], acc[2], acc[3]);
             }
         }
         __syncthreads();
 
-        // ---- scoring: one key per thread and step; TQ scores per key ----
-        const int64_t vis_last = t0 + TQ - 1 + off;                     // last key any query of the tile sees
-        const int64_t kmax = (vis_last + 1 < a.L) ? vis_last + 1 : a.L;
+        // ---- scoring: one key per thread and step, four scores per key ----
         for (int64_t l = tid; l < kmax; l += kPfThreads) {
-            uint32_t w[(M + 3) / 4];
-            const uint8_t *cp = codes_bh + l * M;
-            if constexpr (M == 2) {
-                w[0] = *reinterpret_cast<const uint16_t *>(cp);
-            } else if constexpr (M == 4) {
-                w[0] = *reinterpret_cast<const uint32_t *>(cp);
-            } else if constexpr (M == 8) {
-                const pf_v2u t = *reinterpret_cast<const pf_v2u *>(cp);
-                w[0] = t.x;
-                w[1] = t.y;
-            } else {
-                const pf_v4u t = *reinterpret_cast<const pf_v4u *>(cp);
-                w[0] = t.x;
-                w[1] = t.y;
-                w[2] = t.z;
-                w[3] = t.w;
-            }
-            float s[TQ];
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int t = 0; t < TQ; ++t)
-                s[t] = 0.f;
+            for (int i0 = 0; i0 < M; i0 += GB) {
+                float4 v[GB];
 #pragma unroll
-            for (int i = 0; i < M; ++i) {
-                const uint32_t byte = (w[i / 4] >> (8 * (i % 4))) & 0xffu;
-                const float4 *e = reinterpret_cast<const float4 *>(lut_s + (i * kCentroids + byte) * TQ);
+                for (int u = 0; u < GB; ++u)
+                    v[u] = *reinterpret_cast<const float4 *>(lut_s + ((i0 + u) * kCentroids + kc.byte(i0 + u)) * TQ);
 #pragma unroll
-                for (int t4 = 0; t4 < TQ / 4; ++t4) {
-                    const float4 v = e[t4];
-                    s[4 * t4] += v.x;
-                    s[4 * t4 + 1] += v.y;
-                    s[4 * t4 + 2] += v.z;
-                    s[4 * t4 + 3] += v.w;
+                for (int u = 0; u < GB; ++u) {   // ascending subspace order, as Algorithm 1 sums
+                    s.x += v[u].x;
+                    s.y += v[u].y;
+                    s.z += v[u].z;
+                    s.w += v[u].w;
                 }
             }
+            const int64_t ln = l + kPfThreads;
+            if (ln < kmax)
+                kc.load(codes_bh + ln * M);   // next key of this thread
+            const float sv[TQ] = {s.x, s.y, s.z, s.w};
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 const int tq = t0 + t;
                 if (tq < a.T)
-                    scores_bh[(int64_t)tq * a.L + l] = (l <= tq + off) ? s[t] : -INFINITY;
+                    scores_bh[(int64_t)tq * a.L + l] = (l <= tq + off) ? sv[t] : -INFINITY;
             }
         }
         // ---- keys no query of the tile may see ----
@@ -170,19 +199,20 @@ __global__ __launch_bounds__(kPfThreads) void score_prefill_kernel(const Prefill
 template <typename QT, int DK, int M>
 static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
 {
-    constexpr int TQ = 8;
     PrefillArgs a = a0;
-    a.tiles = (a.T + TQ - 1) / TQ;
-    const size_t lds = ((size_t)M * kCentroids * TQ + (size_t)TQ * DK) * sizeof(float);
-    auto kern = score_prefill_kernel<QT, DK, M, TQ>;
-    static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return fail(LOOKAT_ERR_HIP, "lookat_score_prefill: cannot reserve %zu bytes of LDS: %s", lds,
-                        hipGetErrorString(e));
-        configured = true;
+    a.tiles = (a.T + kPfTQ - 1) / kPfTQ;
+    const size_t lds = ((size_t)M * kCentroids * kPfTQ + (size_t)kPfTQ * DK) * sizeof(float);
+    auto kern = score_prefill_kernel<QT, DK, M>;
+    if (lds > 64 * 1024) {
+        static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS
+        if (!configured) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess)
+                return fail(LOOKAT_ERR_HIP, "lookat_score_prefill: cannot reserve %zu bytes of LDS: %s", lds,
+                            hipGetErrorString(e));
+            configured = true;
+        }
     }
     dim3 grid((unsigned)((a.tiles + kPfGroup - 1) / kPfGroup), (unsigned)BH);
     hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);

@@ -138,6 +138,35 @@ int lookat_attend_decode(const lookat_shape *shape, int64_t L,
                          float *out, float *scores_out,
                          void *stream);
 
+/*
+ * Fused decode step: the three calls a decode step makes per layer, in one kernel.
+ * For every (b,h):
+ *   1. the new token's key k_new[b,h,:] is encoded by the rule of lookat_encode_keys and its m
+ *      codes are written to row L-1 of the code cache (paper Sec. 3.4 "Encoding");
+ *   2. the query's lookup tables are built as in lookat_build_lut (Sec. 3.5), kept on chip;
+ *   3. the query attends over the L cached keys as in lookat_attend_decode (Algorithm 1).
+ * Results equal those of the three separate calls (codes bit for bit; out within fp32
+ * rounding).  Each workgroup re-reads its head's codebook from L2; with few (b,h) pairs and a
+ * long context the three separate calls (which can cut the sequence into ranges) are faster.
+ *
+ *   L          cached keys per (b,h) INCLUDING the new one, >= 1
+ *   q, k_new   [B,H,d_k], both of type qk_dtype (fp16 or fp32), 16-byte aligned, dense
+ *   codes      code cache, element (b,h,l,i) at codes[(b*H+h)*code_stride_bh + l*m + i];
+ *              rows 0..L-2 are read, row L-1 is written (its previous content is ignored)
+ *   values     value cache as in lookat_attend_decode; row L-1 must already hold the new
+ *              token's value
+ *   out        [B,H,d_k] fp32
+ * Supported shapes: d_k in {64, 128}, m in {2, 4, 8, 16}; others: LOOKAT_ERR_UNSUPPORTED.
+ */
+int lookat_decode_step(const lookat_shape *shape, int64_t L,
+                       const void *q, const void *k_new, int qk_dtype,
+                       const float *codebooks,
+                       uint8_t *codes, int64_t code_stride_bh,
+                       const void *values, int64_t value_stride_bh,
+                       float scale,
+                       float *out,
+                       void *stream);
+
 /* The split count lookat_attend_decode uses when num_splits == 0 (host only,
  * no HIP call); 0 if the shape is invalid. */
 int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);

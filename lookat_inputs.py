@@ -125,7 +125,7 @@ def torch_generator(cfg: Config, device, salt: int = 0):
     return g
 
 
-def torch_lowrank_keys(A, lead: tuple, n: int, noise: float, gen, dtype, chunk: int = 1 << 22):
+def torch_lowrank_keys(A, lead: tuple, n: int, noise: float, gen, dtype, chunk: int = 1 << 20):
     """A [H,r,d_k] device fp32 -> keys [*lead,H,n,d_k] of `dtype`, drawn in chunks."""
     import torch
     H, r, d_k = A.shape
@@ -138,7 +138,9 @@ def torch_lowrank_keys(A, lead: tuple, n: int, noise: float, gen, dtype, chunk: 
                 e = min(n, s + rows)
                 z = torch.randn((e - s, r), generator=gen, device=A.device, dtype=torch.float32)
                 eps = torch.randn((e - s, d_k), generator=gen, device=A.device, dtype=torch.float32)
-                flat[b, h, s:e] = (z @ A[h] + noise * eps).to(dtype)
+                # z A_h as broadcast-multiply + reduce: plain elementwise kernels, no BLAS call
+                mix = (z.unsqueeze(2) * A[h].unsqueeze(0)).sum(dim=1)
+                flat[b, h, s:e] = (mix + noise * eps).to(dtype)
     return out
 
 

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     load_library,
     lookat_attend_decode,
     lookat_build_lut,
+    lookat_decode_step,
     lookat_encode_keys,
     lookat_kmeans,
     lookat_kmeans_step,
@@ -28,6 +29,6 @@ from .binding import (  # noqa: F401
 __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
-    "lookat_attend_decode", "lookat_build_lut", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
+    "lookat_attend_decode", "lookat_build_lut", "lookat_decode_step", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
     "lookat_probe_stream_read", "lookat_score_prefill",
 ]

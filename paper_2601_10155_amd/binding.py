@@ -54,6 +54,8 @@ def load_library():
         lib.lookat_attend_decode_auto_splits.restype = i32
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_decode_step.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, vp, vp]
+        lib.lookat_decode_step.restype = ctypes.c_int
         lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
         lib.lookat_score_prefill.restype = ctypes.c_int
         lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
@@ -212,6 +214,37 @@ def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.T
                                     values.data_ptr(), vs, float(scale), int(num_splits), ws_ptr, ws_bytes,
                                     out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
                                     _stream(values)))
+    return out
+
+
+def lookat_decode_step(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
+                       values: torch.Tensor, scale: float, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Fused decode step.  q, k_new [B,H,d_k] (same dtype), codes [B,H,L,m] u8 (row L-1 is written),
+    values [B,H,L,d_k] fp16 (row L-1 already holds the new value) -> out [B,H,d_k] fp32.
+    codes / values may be views of longer caches sliced to L rows."""
+    lib = load_library()
+    q = _dev(q, "q").contiguous()
+    k_new = _dev(k_new, "k_new").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    _dev(codes, "codes"), _dev(values, "values")
+    B, H, L, m = codes.shape
+    d_k = values.shape[3]
+    if q.dtype != k_new.dtype or q.numel() != B * H * d_k or k_new.numel() != B * H * d_k:
+        raise ValueError("q and k_new must both be [B,H,d_k] of one dtype")
+    if cb.dtype != torch.float32 or tuple(cb.shape) != (H, m, 256, d_k // m):
+        raise ValueError("codebooks must be fp32 [H,m,256,d_k/m]")
+    if codes.dtype != torch.uint8 or values.dtype != torch.float16 or tuple(values.shape[:3]) != (B, H, L):
+        raise ValueError("codes must be uint8 [B,H,L,m] and values fp16 [B,H,L,d_k]")
+    cs = _bh_stride(codes, "codes")
+    vs = _bh_stride(values, "values")
+    if out is None:
+        out = torch.empty((B, H, d_k), dtype=torch.float32, device=values.device)
+    if out.dtype != torch.float32 or out.numel() != B * H * d_k or not out.is_contiguous():
+        raise ValueError("out must be contiguous fp32 [B,H,d_k]")
+    shape = _Shape(B, H, d_k, m, 256)
+    _check(lib.lookat_decode_step(ctypes.byref(shape), L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
+                                  cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
+                                  out.data_ptr(), _stream(values)))
     return out
 
 

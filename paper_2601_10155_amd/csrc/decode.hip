@@ -13,6 +13,7 @@
 //   * the sequence is cut into `splits` ranges per (b,h) (flash-decoding style); the
 //     ranges are merged by a second small kernel.
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -40,6 +41,12 @@ struct DecodeArgs {
     int d_k;
     int m;
     float scale_log2e;       // scale * log2(e): the softmax runs in base 2
+    // fused decode step only (lookat_decode_step): the table is built and the new key encoded in-kernel
+    const void *q;           // [BH, d_k]
+    const void *k_new;       // [BH, d_k]
+    const float *codebooks;  // [H, m, 256, d_sub]
+    uint8_t *codes_w;        // same cache as `codes`, writable: row L-1 receives the new key's codes
+    int H;
 };
 
 // Workgroup id -> (bh, split).  Consecutive workgroup ids land on different dies, each
@@ -154,6 +161,82 @@ __device__ __forceinline__ void load_rows(v4u (&v)[CH], __amdgpu_buffer_rsrc_t r
         v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, kb * (DK * 2) + (g0 + j) * kGroupBytes + lane * 16, 0, 0);
 }
 
+// ---- pieces of the fused decode step ---------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float step_f32(T v);
+template <>
+__device__ __forceinline__ float step_f32<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float step_f32<__half>(__half v) { return __half2float(v); }
+
+// Squared distance of the encoder (paper Sec. 3.4 "Encoding"), exactly as lookat_encode_keys
+// evaluates it: fp64, ascending coordinates, one rounding per subtract, multiply and add.
+template <typename KT, int DSUB>
+__device__ __forceinline__ double step_sq_dist(const KT *__restrict__ x, const float (&y)[DSUB])
+{
+#pragma clang fp contract(off)
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < DSUB; ++j) {
+        double diff = (double)step_f32<KT>(x[j]) - (double)y[j];
+        double sq = diff * diff;
+        acc = acc + sq;
+    }
+    return acc;
+}
+
+// (distance, centroid) pairs ordered as the encoder's serial scan orders them: smaller
+// distance first, then smaller index; a NaN distance is last, except centroid 0's (first).
+struct ArgMin {
+    uint32_t lo, hi;   // order key of the distance (bit pattern of a non-negative double)
+    int c;
+};
+__device__ __forceinline__ ArgMin argmin_make(double d, int c)
+{
+    uint64_t k = (d != d) ? (c == 0 ? 0ull : ~0ull) : (uint64_t)__double_as_longlong(d);
+    return ArgMin{(uint32_t)k, (uint32_t)(k >> 32), c};
+}
+__device__ __forceinline__ ArgMin argmin_pick(const ArgMin &a, const ArgMin &b)
+{
+    const bool b_first = (b.hi < a.hi) || (b.hi == a.hi && (b.lo < a.lo || (b.lo == a.lo && b.c < a.c)));
+    ArgMin r;   // field-wise selects (a struct select would go through memory)
+    r.lo = b_first ? b.lo : a.lo;
+    r.hi = b_first ? b.hi : a.hi;
+    r.c = b_first ? b.c : a.c;
+    return r;
+}
+template <int CTRL>
+__device__ __forceinline__ ArgMin argmin_dpp(const ArgMin &a)
+{
+    ArgMin b;
+    b.lo = (uint32_t)__builtin_amdgcn_update_dpp((int)a.lo, (int)a.lo, CTRL, 0xf, 0xf, false);
+    b.hi = (uint32_t)__builtin_amdgcn_update_dpp((int)a.hi, (int)a.hi, CTRL, 0xf, 0xf, false);
+    b.c = __builtin_amdgcn_update_dpp(a.c, a.c, CTRL, 0xf, 0xf, false);
+    return argmin_pick(a, b);
+}
+// minimum over the wavefront; every lane ends with it
+__device__ __forceinline__ ArgMin argmin_wave(ArgMin a)
+{
+    a = argmin_dpp<0xB1>(a);    // lane ^ 1
+    a = argmin_dpp<0x4E>(a);    // lane ^ 2
+    a = argmin_dpp<0x141>(a);   // other quad of each 8
+    a = argmin_dpp<0x140>(a);   // other 8 of each 16
+    ArgMin b;
+    {
+        const auto l = __builtin_amdgcn_permlane16_swap(a.lo, a.lo, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap(a.hi, a.hi, false, false);
+        const auto c = __builtin_amdgcn_permlane16_swap((uint32_t)a.c, (uint32_t)a.c, false, false);
+        a = argmin_pick(ArgMin{l[0], h[0], (int)c[0]}, ArgMin{l[1], h[1], (int)c[1]});
+    }
+    {
+        const auto l = __builtin_amdgcn_permlane32_swap(a.lo, a.lo, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap(a.hi, a.hi, false, false);
+        const auto c = __builtin_amdgcn_permlane32_swap((uint32_t)a.c, (uint32_t)a.c, false, false);
+        b = argmin_pick(ArgMin{l[0], h[0], (int)c[0]}, ArgMin{l[1], h[1], (int)c[1]});
+    }
+    return b;
+}
+
 // Online-softmax state of one wavefront (base-2 exponent domain).
 struct SoftmaxState {
     float m_run = -INFINITY;   // running max of scale*log2e*s over the keys seen so far
@@ -164,15 +247,41 @@ struct SoftmaxState {
 // One 64-key tile of a wavefront: its codes (kc) and first CH value-row groups (v) are in
 // registers or in flight.  Scores one key per lane (key = kb + kofs), updates the running
 // max / sum, and accumulates the weighted value rows.
-template <int DK, int M, int CH>
-__device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &st, const KeyCodes<M ? M : 4> &kc,
+template <int DK, int M, int CH, bool FUSED = false>
+__device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &st, const KeyCodes<M ? M : 4> &kc_in,
                                              v4u (&v)[CH], const float *lut_s, __amdgpu_buffer_rsrc_t rc,
                                              __amdgpu_buffer_rsrc_t rv, int bh, uint32_t kb, uint32_t k1,
-                                             uint32_t kofs, int lane, int m)
+                                             uint32_t kofs, int lane, int m, const ArgMin *enc_s = nullptr)
 {
     constexpr int LPR = DK / 8;
     constexpr int NLD = LPR;
     const uint32_t key = kb + kofs;
+    KeyCodes<M ? M : 4> kc = kc_in;
+    if constexpr (FUSED) {
+        // The newest key (row L-1) was encoded by this workgroup a moment ago: the lane that
+        // scores it merges the per-wave minima, uses those codes and appends them to the cache.
+        if (key == (uint32_t)(a.L - 1)) {
+#pragma unroll
+            for (int w = 0; w < (M + 3) / 4; ++w)
+                kc.w[w] = 0u;
+#pragma unroll
+            for (int i = 0; i < M; ++i) {
+                ArgMin best = enc_s[i * kDecWaves];
+#pragma unroll
+                for (int w = 1; w < kDecWaves; ++w)
+                    best = argmin_pick(best, enc_s[i * kDecWaves + w]);
+                kc.w[i / 4] |= (uint32_t)best.c << (8 * (i % 4));
+            }
+            uint8_t *dst = a.codes_w + (int64_t)bh * a.code_stride + (int64_t)key * M;
+            if constexpr (M == 2) {
+                *reinterpret_cast<uint16_t *>(dst) = (uint16_t)kc.w[0];
+            } else {
+#pragma unroll
+                for (int w = 0; w < M / 4; ++w)
+                    reinterpret_cast<uint32_t *>(dst)[w] = kc.w[w];
+            }
+        }
+    }
     float raw;
     if constexpr (M != 0)
         raw = kc.score(lut_s);
@@ -203,9 +312,14 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &
 
 // DK in {32, 64, 128, 256}; M in {2, 4, 8, 16} or 0 (= runtime m, byte loads);
 // WAVES wavefronts per workgroup, OCC = wavefronts per SIMD the register budget must allow.
-template <int DK, int M, int WAVES, int OCC>
+// FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused
+// decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
+// the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
+template <int DK, int M, int WAVES, int OCC, typename FT = void>
 __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const DecodeArgs a)
 {
+    constexpr bool FUSED = !std::is_void<FT>::value;
+    static_assert(!FUSED || (WAVES == kDecWaves && M != 0), "fused step: 256 threads, compile-time m");
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
     constexpr int RPL = kWave / LPR;       // value rows covered by one wave-wide load
     constexpr int NLD = kTile / RPL;       // wave-wide loads per tile (= LPR)
@@ -215,6 +329,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                                   // [m][256]
     float *red_s = smem + (M ? M : a.m) * kCentroids;      // [WAVES][DK + 2]
+    ArgMin *enc_s = reinterpret_cast<ArgMin *>(red_s + WAVES * (DK + 2));   // fused step: [M][WAVES]
 
     int bh, split;
     if (!map_block(a, bh, split))
@@ -236,11 +351,13 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
     const float4 *lut_g = reinterpret_cast<const float4 *>(a.lut + (int64_t)bh * m * kCentroids);
     constexpr int kLutRegs = M ? (M * (kCentroids / 4) + NT - 1) / NT : 1;
     float4 lut_r[kLutRegs];
-    if constexpr (M != 0) {
+    if constexpr (M != 0 && !FUSED) {
 #pragma unroll
         for (int x = 0; x < kLutRegs; ++x)
-            if (tid + x * NT < M * (kCentroids / 4))
+            if ((x + 1) * NT <= M * (kCentroids / 4) || tid + x * NT < M * (kCentroids / 4))
                 lut_r[x] = lut_g[tid + x * NT];
+            else
+                lut_r[x] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
     // 2) the codes of the wave's first tile;  3) its value rows.
     // Lane (rowin, sub) holds the value rows RPL*j + rowin, j = 0..NLD-1, of a tile.  It scores
@@ -255,31 +372,78 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
         kc.load(rc, (kb + kofs) * M);
     v4u v[CH];
     load_rows<DK, CH>(v, rv, kb, 0, lane);
-    {
+    if constexpr (FUSED) {
+        // While the first tile is in flight: thread c takes centroid c of each subspace from the
+        // (L2-resident) codebook of the head, and from the same row computes
+        //   the table entry  LUT_i[c] = q^(i) . C_i[c]           (Sec. 3.5, fp32, ascending j)
+        //   the distance     || k_new^(i) - C_i[c] ||^2          (Sec. 3.4, fp64, as the encoder)
+        // q and k_new are read at wave-uniform addresses.  Subspaces are processed in groups
+        // whose rows fit 64 registers, all rows of a group requested together.
+        constexpr int DSUB = DK / M;
+        constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
+        const int h = bh % a.H;
+        const FT *__restrict__ qg = static_cast<const FT *>(a.q) + (int64_t)bh * DK;
+        const FT *__restrict__ kg = static_cast<const FT *>(a.k_new) + (int64_t)bh * DK;
+        const float *__restrict__ cbh = a.codebooks + (int64_t)h * M * kCentroids * DSUB + (int64_t)tid * DSUB;
+#pragma unroll
+        for (int i0 = 0; i0 < M; i0 += GS) {
+            float row[GS][DSUB];
+#pragma unroll
+            for (int g = 0; g < GS; ++g) {
+                const float4 *src = reinterpret_cast<const float4 *>(cbh + (int64_t)(i0 + g) * kCentroids * DSUB);
+                if constexpr (DSUB % 4 == 0) {
+#pragma unroll
+                    for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+                        const float4 t4 = src[j4];
+                        row[g][4 * j4] = t4.x;
+                        row[g][4 * j4 + 1] = t4.y;
+                        row[g][4 * j4 + 2] = t4.z;
+                        row[g][4 * j4 + 3] = t4.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < DSUB; ++j)
+                        row[g][j] = reinterpret_cast<const float *>(src)[j];
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < GS; ++g) {
+                const int i = i0 + g;
+                float e = 0.f;
+#pragma unroll
+                for (int j = 0; j < DSUB; ++j)
+                    e = fmaf(step_f32<FT>(qg[i * DSUB + j]), row[g][j], e);
+                lut_s[i * kCentroids + tid] = e;
+                const ArgMin best = argmin_wave(argmin_make(step_sq_dist<FT, DSUB>(kg + i * DSUB, row[g]), tid));
+                if (lane == 0)
+                    enc_s[i * kDecWaves + wave] = best;
+            }
+        }
+    } else {
         float4 *s4 = reinterpret_cast<float4 *>(lut_s);
         if constexpr (M != 0) {
 #pragma unroll
             for (int x = 0; x < kLutRegs; ++x)
-                if (tid + x * NT < M * (kCentroids / 4))
+                if ((x + 1) * NT <= M * (kCentroids / 4) || tid + x * NT < M * (kCentroids / 4))
                     s4[tid + x * NT] = lut_r[x];
         } else {
             for (int x = tid; x < m * (kCentroids / 4); x += NT)
                 s4[x] = lut_g[x];
         }
     }
-    __syncthreads();   // table complete in LDS (the value rows stay in flight)
+    __syncthreads();   // table (and, fused, the per-wave argmins) complete in LDS; value rows stay in flight
 
     // First tile (requested above), then the wave's remaining tiles: request, consume.  Tiles
     // are requested only if they exist (a load past the range would return zero but still
     // occupy the address pipeline), and a tile's registers are dead at the loop back-edge.
     SoftmaxState st;
     if (kb < k1) {
-        consume_tile<DK, M, CH>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m);
+        consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_s);
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
             load_rows<DK, CH>(v, rv, kb, 0, lane);
-            consume_tile<DK, M, CH>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m);
+            consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_s);
         }
     }
     float m_run = st.m_run, z = st.z;
@@ -491,7 +655,99 @@ static int pick_waves(int d_k, int m, int64_t keys_per_split)
     return keys_per_split >= 32 * kTile ? 16 : 4;
 }
 
+// Fused decode step: one workgroup of 256 threads per (b,h), one range.
+template <int DK, typename FT>
+static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    dim3 block(kDecThreads);
+    const size_t lds = ((size_t)a.m * kCentroids + (size_t)kDecWaves * (DK + 2)) * sizeof(float) +
+                       (size_t)a.m * kDecWaves * sizeof(ArgMin);
+    switch (a.m) {
+    case 2:   // 32- or 64-coordinate rows: give the register allocator the larger budget
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT>), grid, block, lds, st, a);
+        return true;
+    case 4:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        return true;
+    case 8:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        return true;
+    case 16:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        return true;
+    default:
+        return false;
+    }
+}
+
 }  // namespace lookat
+
+extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
+                                  int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                  const void *values, int64_t value_stride_bh, float scale, float *out, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (L <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
+    if (qk_dtype != LOOKAT_F16 && qk_dtype != LOOKAT_F32)
+        return fail(LOOKAT_ERR_DTYPE, "qk_dtype=%d is neither LOOKAT_F16 nor LOOKAT_F32", qk_dtype);
+    if (!q || !k_new || !codebooks || !codes || !values || !out)
+        return fail(LOOKAT_ERR_NULL, "q, k_new, codebooks, codes, values and out must be non-NULL");
+    if (code_stride_bh < L * shape->m || value_stride_bh < L * shape->d_k)
+        return fail(LOOKAT_ERR_SHAPE, "code_stride_bh=%lld / value_stride_bh=%lld smaller than one (b,h) slab",
+                    (long long)code_stride_bh, (long long)value_stride_bh);
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(codebooks) || !aligned16(values) || !aligned16(out) ||
+        ((value_stride_bh * 2) % 16))
+        return fail(LOOKAT_ERR_ALIGN, "q, k_new, codebooks, values, out and value_stride_bh must be 16-byte aligned");
+    const bool m_ok = shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16;
+    if (!m_ok || (shape->d_k != 64 && shape->d_k != 128))
+        return fail(LOOKAT_ERR_UNSUPPORTED,
+                    "lookat_decode_step handles d_k in {64,128} with m in {2,4,8,16}; got d_k=%d m=%d "
+                    "(use encode_keys + build_lut + attend_decode)", shape->d_k, shape->m);
+    if ((reinterpret_cast<uintptr_t>(codes) % shape->m) || (code_stride_bh % shape->m))
+        return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of m=%d bytes", shape->m);
+    if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
+    const int64_t BH = (int64_t)shape->B * shape->H;
+    const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds;
+    if (nblocks > 0x7fffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H=%lld workgroups exceed one launch", (long long)BH);
+
+    DecodeArgs a;
+    a.lut = nullptr;
+    a.codes = codes;
+    a.values = static_cast<const __half *>(values);
+    a.part = nullptr;
+    a.out = out;
+    a.scores_out = nullptr;
+    a.code_stride = code_stride_bh;
+    a.value_stride = value_stride_bh;
+    a.L = L;
+    a.keys_per_split = round_up(L, kTile);
+    a.BH = (int)BH;
+    a.splits = 1;
+    a.d_k = shape->d_k;
+    a.m = shape->m;
+    a.scale_log2e = scale * kLog2e;
+    a.q = q;
+    a.k_new = k_new;
+    a.codebooks = codebooks;
+    a.codes_w = codes;
+    a.H = shape->H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)nblocks);
+    bool ok;
+    if (shape->d_k == 64)
+        ok = (qk_dtype == LOOKAT_F16) ? launch_step<64, __half>(a, grid, st) : launch_step<64, float>(a, grid, st);
+    else
+        ok = (qk_dtype == LOOKAT_F16) ? launch_step<128, __half>(a, grid, st) : launch_step<128, float>(a, grid, st);
+    if (!ok)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "no fused kernel for this shape");
+    return check_launch("lookat_decode_step");
+}
 
 extern "C" int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L)
 {
@@ -576,6 +832,11 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     a.d_k = shape->d_k;
     a.m = shape->m;
     a.scale_log2e = scale * kLog2e;
+    a.q = nullptr;
+    a.k_new = nullptr;
+    a.codebooks = nullptr;
+    a.codes_w = nullptr;
+    a.H = shape->H;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)nblocks);

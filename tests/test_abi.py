@@ -31,7 +31,7 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
-            "lookat_probe_stream_read", "lookat_score_prefill"} <= set(names)
+            "lookat_probe_stream_read", "lookat_score_prefill", "lookat_decode_step"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -140,4 +140,25 @@ def test_score_prefill_argument_errors(lib):
     assert call(codes=FAKE + 8) == E_ALIGN
     bad = Shape(2, 3, 96, 4, 256)
     a = list(ok_args); a[0] = ctypes.byref(bad); a[7] = 64 * 4
+    assert f(*a) == E_UNSUP
+
+
+def test_decode_step_argument_errors(lib):
+    s = Shape(2, 3, 64, 4, 256)
+    f = lib.lookat_decode_step
+    L = 100
+    base = [ctypes.byref(s), L, FAKE, FAKE, 1, FAKE, FAKE, L * 4, FAKE, L * 64, ctypes.c_float(0.125), FAKE, None]
+    def call(**kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[{"L": 1, "q": 2, "k": 3, "dt": 4, "cb": 5, "codes": 6, "cs": 7, "values": 8, "vs": 9, "out": 11}[k]] = v
+        return f(*a)
+    assert call(L=0) == E_SHAPE
+    assert call(dt=3) == E_DTYPE
+    assert call(k=None) == E_NULL
+    assert call(cs=L * 4 - 4) == E_SHAPE
+    assert call(q=FAKE + 4) == E_ALIGN
+    assert call(codes=FAKE + 2) == E_ALIGN
+    bad = Shape(2, 3, 32, 4, 256)
+    a = list(base); a[0] = ctypes.byref(bad); a[9] = L * 32
     assert f(*a) == E_UNSUP

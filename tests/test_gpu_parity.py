@@ -365,3 +365,54 @@ def test_score_prefill_matches_decode_rows(lk):
                                 0.1, scores_out=s)
         d = np.abs(block[:, :, t, :t + 1] - s.cpu().numpy())
         assert d.max() <= 1e-5
+
+
+# ---------------------------------------------------------------- fused decode step ----
+
+def _step_reference(case, cb, L, scale):
+    """The three oracle calls a decode step consists of: encode key L-1, build tables, attend."""
+    keys, q, v = case["keys"][:, :, :L], case["q"], case["values"][:, :, :L]
+    codes = oracle.encode_keys(keys, cb)
+    lut = oracle.build_lut(q, cb)[:, :, 0]
+    out = oracle.attend_decode(lut, codes, v, scale)
+    return codes, out
+
+
+@pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (64, 8), (64, 16), (128, 8), (128, 16), (128, 2), (128, 4)])
+@pytest.mark.parametrize("qk_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("L", [1, 64, 65, 300, 1024])
+def test_decode_step_matches_oracle(lk, d_k, m, qk_dtype, L):
+    B, H, Lmax = 2, 5, 1100
+    cfg = li.shrink(li.CONFIGS["C2"], B=B, H=H, L=Lmax, d_k=d_k, m=m, n_calib=400, key_dtype=qk_dtype,
+                    q_dtype=qk_dtype, rank=8 if d_k == 64 else 16)
+    case = li.make_case(cfg, seed=6000 + d_k + m)
+    cb = case["cb_init"]
+    scale = 1.0 / math.sqrt(d_k)
+    codes_ref, out_ref = _step_reference(case, cb, L, scale)
+    # cache as a serving loop holds it: rows 0..L-2 coded, row L-1 stale, capacity Lmax
+    cache = torch.full((B, H, Lmax, m), 0xAB, dtype=torch.uint8, device="cuda")
+    cache[:, :, :L - 1] = dev(codes_ref[:, :, :L - 1])
+    values = dev(case["values"])
+    k_new = dev(case["keys"][:, :, L - 1])
+    out = lk.lookat_decode_step(dev(case["q"][:, :, 0]), k_new, dev(cb), cache[:, :, :L], values[:, :, :L], scale)
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[:, :, :L], codes_ref), "code cache after the step"
+    assert (got[:, :, L:] == 0xAB).all(), "rows past L were touched"
+    assert np.max(np.abs(out.cpu().numpy() - out_ref)) <= OUT_ATOL
+
+
+def test_decode_step_equals_three_calls(lk):
+    """Same shape as one layer of the GPT-2-small batch-32 workload, reduced batch."""
+    cfg = li.shrink(li.CONFIGS["C2"], B=4, n_calib=1024)
+    case = li.make_case(cfg, seed=6100)
+    cb = lk.lookat_kmeans(dev(case["calib"]), dev(case["cb_init"]), 2)
+    scale = 0.125
+    keys, values, q = dev(case["keys"]), dev(case["values"]), dev(case["q"]).float()   # one dtype for q and keys
+    codes3 = lk.lookat_encode_keys(keys, cb)
+    lut = lk.lookat_build_lut(q, cb)
+    out3 = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes3, values, scale)
+    cache = codes3.clone()
+    cache[:, :, -1] = 0
+    out1 = lk.lookat_decode_step(q[:, :, 0], keys[:, :, -1], cb, cache, values, scale)
+    assert torch.equal(cache, codes3)
+    assert float((out1 - out3).abs().max()) <= 1e-5

@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3"])
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
+    ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
+                    help="fused: one lookat_decode_step per layer; calls: encode_keys + build_lut + attend_decode; "
+                         "auto: fused when the library would use a single range per (b,h)")
     ap.add_argument("--kmeans-iters", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
@@ -50,6 +53,9 @@ class Layer:
         self.cb = lk.lookat_kmeans(case["calib"], case["cb_init"], kmeans_iters)
         self.codes = lk.lookat_encode_keys(case["keys"], self.cb)           # [B,H,L,m] code cache
         self.new_key = case["keys"][:, :, cfg.L - 1:cfg.L].contiguous()      # the step's new token
+        # the fused step takes q and the new key in one dtype (fp16 -> fp32 widening is exact)
+        self.q_step = case["q"][:, :, 0].to(self.new_key.dtype).contiguous()
+        self.k_step = self.new_key[:, :, 0].contiguous()
         self.values = case["values"]
         self.q = case["q"]
         self.lut = torch.empty((cfg.B, cfg.H, 1, cfg.m, cfg.K), dtype=torch.float32, device=device)
@@ -88,11 +94,20 @@ def main():
         lk.lookat_attend_decode(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
                                 num_splits=splits, workspace=workspace, out=ly.out)
 
+    fused = args.path == "fused" or (args.path == "auto" and splits == 1 and cfg.d_k in (64, 128)
+                                     and cfg.m in (2, 4, 8, 16))
+
+    def fused_only(ly):
+        lk.lookat_decode_step(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)
+
     def step():
         for ly in layers:
-            lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
-            lk.lookat_build_lut(ly.q, ly.cb, lut_out=ly.lut)
-            decode_only(ly)
+            if fused:
+                fused_only(ly)
+            else:
+                lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
+                lk.lookat_build_lut(ly.q, ly.cb, lut_out=ly.lut)
+                decode_only(ly)
 
     # ---- one eager step: its outputs are the reference for the graph replays ----------
     step()
@@ -138,16 +153,23 @@ def main():
     #      the layers' distinct caches (so no launch re-reads what the last-level cache holds) ----
     bytes_per_launch = cfg.B * cfg.H * cfg.L * (cfg.m + 2 * cfg.d_k)
     n_launch = max(args.steps, 20) * cfg.layers
-    for ly in layers:
-        decode_only(ly)
-    torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(n_launch):
-        decode_only(layers[i % cfg.layers])
-    e1.record()
-    torch.cuda.synchronize()
-    us_per_launch = e0.elapsed_time(e1) * 1e3 / n_launch
+
+    def time_launches(fn):
+        for ly in layers:
+            fn(ly)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n_launch):
+            fn(layers[i % cfg.layers])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n_launch
+
+    for ly in layers:                     # the tables must exist for the stand-alone decode launches
+        lk.lookat_build_lut(ly.q, ly.cb, lut_out=ly.lut)
+    us_decode_alone = time_launches(decode_only)
+    us_per_launch = time_launches(fused_only) if fused else us_decode_alone
     achieved = bytes_per_launch / us_per_launch / 1e3   # GB/s
 
     # plain read stream over the same value caches: what the HBM read path delivers here
@@ -179,13 +201,15 @@ def main():
         "config": {
             "workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d_k={cfg.d_k} m={cfg.m} K={cfg.K} "
                         f"layers={cfg.layers}; per layer encode(1 new key) + build_lut + attend_decode",
+            "path": "lookat_decode_step (one fused kernel per layer)" if fused
+                    else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode",
             "values": "fp16", "codes": "u8", "lut": "f32", "launch": args.mode, "num_splits": splits,
             "codebooks": f"{args.kmeans_iters} Lloyd iterations (lookat_kmeans_step) on {cfg.n_calib} seeded "
                          "calibration keys per head",
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "lookat::decode_split_kernel",
+            "kernel": "lookat::decode_split_kernel" + (" (fused step instance)" if fused else ""),
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -194,6 +218,8 @@ def main():
             "bytes_per_launch": bytes_per_launch,
             "us_per_launch": us_per_launch,
             "launches_timed": n_launch,
+            "attend_decode_alone_us": us_decode_alone,
+            "attend_decode_alone_GBs": bytes_per_launch / us_decode_alone / 1e3,
             "read_stream_GBs": stream_gbs,
             "frac_of_read_stream": achieved / stream_gbs,
         },

@@ -171,14 +171,32 @@ __device__ __forceinline__ float step_f32<__half>(__half v) { return __half2floa
 
 // Squared distance of the encoder (paper Sec. 3.4 "Encoding"), exactly as lookat_encode_keys
 // evaluates it: fp64, ascending coordinates, one rounding per subtract, multiply and add.
+// A dense, 16-byte aligned, read-only array of T addressed uniformly over the wavefront, read
+// as 32-bit words through the constant address space: the compiler turns these into scalar
+// loads (an s_load needs dword alignment, which a __half pointer would not promise).
+typedef const __attribute__((address_space(4))) uint32_t *UniformWords;
+template <typename T>
+__device__ __forceinline__ float uniform_elem(UniformWords p, int idx);
+template <>
+__device__ __forceinline__ float uniform_elem<float>(UniformWords p, int idx)
+{
+    return __uint_as_float(p[idx]);
+}
+template <>
+__device__ __forceinline__ float uniform_elem<__half>(UniformWords p, int idx)
+{
+    const uint32_t w = p[idx >> 1];
+    return __half2float(__ushort_as_half((unsigned short)((idx & 1) ? (w >> 16) : (w & 0xffffu))));
+}
+
 template <typename KT, int DSUB>
-__device__ __forceinline__ double step_sq_dist(const KT *__restrict__ x, const float (&y)[DSUB])
+__device__ __forceinline__ double step_sq_dist(UniformWords x, int x0, const float (&y)[DSUB])
 {
 #pragma clang fp contract(off)
     double acc = 0.0;
 #pragma unroll
     for (int j = 0; j < DSUB; ++j) {
-        double diff = (double)step_f32<KT>(x[j]) - (double)y[j];
+        double diff = (double)uniform_elem<KT>(x, x0 + j) - (double)y[j];
         double sq = diff * diff;
         acc = acc + sq;
     }
@@ -312,6 +330,30 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &
 
 // DK in {32, 64, 128, 256}; M in {2, 4, 8, 16} or 0 (= runtime m, byte loads);
 // WAVES wavefronts per workgroup, OCC = wavefronts per SIMD the register budget must allow.
+// Codebook rows of centroid `tid` for the GS subspaces i0 .. i0+GS-1 of one head.
+template <int DSUB, int GS>
+__device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const float *__restrict__ cb_head_c, int i0)
+{
+#pragma unroll
+    for (int g = 0; g < GS; ++g) {
+        const float *src = cb_head_c + (int64_t)(i0 + g) * kCentroids * DSUB;
+        if constexpr (DSUB % 4 == 0) {
+#pragma unroll
+            for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+                const float4 t4 = reinterpret_cast<const float4 *>(src)[j4];
+                row[g][4 * j4] = t4.x;
+                row[g][4 * j4 + 1] = t4.y;
+                row[g][4 * j4 + 2] = t4.z;
+                row[g][4 * j4 + 3] = t4.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < DSUB; ++j)
+                row[g][j] = src[j];
+        }
+    }
+}
+
 // FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused
 // decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
 // the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
@@ -359,6 +401,17 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
             else
                 lut_r[x] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    //    (fused step: instead of a table slice, the first group of codebook rows; they come from
+    //    L2 and are requested FIRST, because loads return in order: behind the value rows they
+    //    would only be usable once the whole tile has arrived)
+    constexpr int FDSUB = (FUSED && M != 0) ? DK / (M ? M : 1) : 1;
+    constexpr int FGS = !FUSED ? 1 : ((64 / FDSUB) < 1 ? 1 : ((64 / FDSUB) > M ? M : (64 / FDSUB)));
+    float frow[FGS][FDSUB];
+    const float *__restrict__ cbh = nullptr;
+    if constexpr (FUSED) {
+        cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * FDSUB + (int64_t)tid * FDSUB;
+        load_centroid_rows<FDSUB, FGS>(frow, cbh, 0);
+    }
     // 2) the codes of the wave's first tile;  3) its value rows.
     // Lane (rowin, sub) holds the value rows RPL*j + rowin, j = 0..NLD-1, of a tile.  It scores
     // the key RPL*sub + rowin, so the NLD weights a lane needs sit in its own group of LPR
@@ -379,42 +432,26 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
         //   the distance     || k_new^(i) - C_i[c] ||^2          (Sec. 3.4, fp64, as the encoder)
         // q and k_new are read at wave-uniform addresses.  Subspaces are processed in groups
         // whose rows fit 64 registers, all rows of a group requested together.
-        constexpr int DSUB = DK / M;
-        constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
-        const int h = bh % a.H;
-        const FT *__restrict__ qg = static_cast<const FT *>(a.q) + (int64_t)bh * DK;
-        const FT *__restrict__ kg = static_cast<const FT *>(a.k_new) + (int64_t)bh * DK;
-        const float *__restrict__ cbh = a.codebooks + (int64_t)h * M * kCentroids * DSUB + (int64_t)tid * DSUB;
+        constexpr int DSUB = FDSUB;
+        constexpr int GS = FGS;
+        // q and k_new are read-only and addressed uniformly over the wavefront: read through the
+        // constant address space they become scalar loads (SGPR operands of the FMAs below) and
+        // stay out of the in-order vector-memory queue that carries the value rows.
+        const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * DK * sizeof(FT));
+        const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
 #pragma unroll
         for (int i0 = 0; i0 < M; i0 += GS) {
-            float row[GS][DSUB];
-#pragma unroll
-            for (int g = 0; g < GS; ++g) {
-                const float4 *src = reinterpret_cast<const float4 *>(cbh + (int64_t)(i0 + g) * kCentroids * DSUB);
-                if constexpr (DSUB % 4 == 0) {
-#pragma unroll
-                    for (int j4 = 0; j4 < DSUB / 4; ++j4) {
-                        const float4 t4 = src[j4];
-                        row[g][4 * j4] = t4.x;
-                        row[g][4 * j4 + 1] = t4.y;
-                        row[g][4 * j4 + 2] = t4.z;
-                        row[g][4 * j4 + 3] = t4.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < DSUB; ++j)
-                        row[g][j] = reinterpret_cast<const float *>(src)[j];
-                }
-            }
+            if (i0 > 0)
+                load_centroid_rows<DSUB, GS>(frow, cbh, i0);
 #pragma unroll
             for (int g = 0; g < GS; ++g) {
                 const int i = i0 + g;
                 float e = 0.f;
 #pragma unroll
                 for (int j = 0; j < DSUB; ++j)
-                    e = fmaf(step_f32<FT>(qg[i * DSUB + j]), row[g][j], e);
+                    e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
                 lut_s[i * kCentroids + tid] = e;
-                const ArgMin best = argmin_wave(argmin_make(step_sq_dist<FT, DSUB>(kg + i * DSUB, row[g]), tid));
+                const ArgMin best = argmin_wave(argmin_make(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid));
                 if (lane == 0)
                     enc_s[i * kDecWaves + wave] = best;
             }

@@ -203,56 +203,56 @@ __device__ __forceinline__ double step_sq_dist(UniformWords x, int x0, const flo
     return acc;
 }
 
-// (distance, centroid) pairs ordered as the encoder's serial scan orders them: smaller
-// distance first, then smaller index; a NaN distance is last, except centroid 0's (first).
-struct ArgMin {
-    uint32_t lo, hi;   // order key of the distance (bit pattern of a non-negative double)
-    int c;
-};
-__device__ __forceinline__ ArgMin argmin_make(double d, int c)
+// Argmin over the 256 centroids with the encoder's rule (strict '<' scan over ascending index).
+// Distances are mapped to an order value: the distance itself; a NaN becomes +inf (it never
+// wins), except at centroid 0, where it becomes -1 (the scan starts there and nothing compares
+// below a NaN).  The smallest order value with the lowest index is then exactly the scan's result.
+__device__ __forceinline__ double argmin_value(double d, int c)
 {
-    uint64_t k = (d != d) ? (c == 0 ? 0ull : ~0ull) : (uint64_t)__double_as_longlong(d);
-    return ArgMin{(uint32_t)k, (uint32_t)(k >> 32), c};
-}
-__device__ __forceinline__ ArgMin argmin_pick(const ArgMin &a, const ArgMin &b)
-{
-    const bool b_first = (b.hi < a.hi) || (b.hi == a.hi && (b.lo < a.lo || (b.lo == a.lo && b.c < a.c)));
-    ArgMin r;   // field-wise selects (a struct select would go through memory)
-    r.lo = b_first ? b.lo : a.lo;
-    r.hi = b_first ? b.hi : a.hi;
-    r.c = b_first ? b.c : a.c;
-    return r;
+    return (d != d) ? (c == 0 ? -1.0 : (double)INFINITY) : d;
 }
 template <int CTRL>
-__device__ __forceinline__ ArgMin argmin_dpp(const ArgMin &a)
+__device__ __forceinline__ double dmin_dpp(double x)
 {
-    ArgMin b;
-    b.lo = (uint32_t)__builtin_amdgcn_update_dpp((int)a.lo, (int)a.lo, CTRL, 0xf, 0xf, false);
-    b.hi = (uint32_t)__builtin_amdgcn_update_dpp((int)a.hi, (int)a.hi, CTRL, 0xf, 0xf, false);
-    b.c = __builtin_amdgcn_update_dpp(a.c, a.c, CTRL, 0xf, 0xf, false);
-    return argmin_pick(a, b);
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)u, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(u >> 32), (int)(uint32_t)(u >> 32), CTRL,
+                                                               0xf, 0xf, false);
+    return fmin(x, __longlong_as_double((long long)(((uint64_t)hi << 32) | lo)));
 }
-// minimum over the wavefront; every lane ends with it
-__device__ __forceinline__ ArgMin argmin_wave(ArgMin a)
+// N independent minima over the wavefront, reduced in lock step (the chains interleave);
+// every lane ends with all N results.
+template <int N>
+__device__ __forceinline__ void dmin_wave(double (&x)[N])
 {
-    a = argmin_dpp<0xB1>(a);    // lane ^ 1
-    a = argmin_dpp<0x4E>(a);    // lane ^ 2
-    a = argmin_dpp<0x141>(a);   // other quad of each 8
-    a = argmin_dpp<0x140>(a);   // other 8 of each 16
-    ArgMin b;
-    {
-        const auto l = __builtin_amdgcn_permlane16_swap(a.lo, a.lo, false, false);
-        const auto h = __builtin_amdgcn_permlane16_swap(a.hi, a.hi, false, false);
-        const auto c = __builtin_amdgcn_permlane16_swap((uint32_t)a.c, (uint32_t)a.c, false, false);
-        a = argmin_pick(ArgMin{l[0], h[0], (int)c[0]}, ArgMin{l[1], h[1], (int)c[1]});
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0xB1>(x[i]);    // lane ^ 1
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x4E>(x[i]);    // lane ^ 2
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x141>(x[i]);   // other quad of each 8
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x140>(x[i]);   // other 8 of each 16
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const uint64_t u = (uint64_t)__double_as_longlong(x[i]);
+        const auto l = __builtin_amdgcn_permlane16_swap((uint32_t)u, (uint32_t)u, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+        x[i] = fmin(__longlong_as_double((long long)(((uint64_t)h[0] << 32) | l[0])),
+                    __longlong_as_double((long long)(((uint64_t)h[1] << 32) | l[1])));
     }
-    {
-        const auto l = __builtin_amdgcn_permlane32_swap(a.lo, a.lo, false, false);
-        const auto h = __builtin_amdgcn_permlane32_swap(a.hi, a.hi, false, false);
-        const auto c = __builtin_amdgcn_permlane32_swap((uint32_t)a.c, (uint32_t)a.c, false, false);
-        b = argmin_pick(ArgMin{l[0], h[0], (int)c[0]}, ArgMin{l[1], h[1], (int)c[1]});
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const uint64_t u = (uint64_t)__double_as_longlong(x[i]);
+        const auto l = __builtin_amdgcn_permlane32_swap((uint32_t)u, (uint32_t)u, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+        x[i] = fmin(__longlong_as_double((long long)(((uint64_t)h[0] << 32) | l[0])),
+                    __longlong_as_double((long long)(((uint64_t)h[1] << 32) | l[1])));
     }
-    return b;
 }
 
 // Online-softmax state of one wavefront (base-2 exponent domain).
@@ -269,7 +269,7 @@ template <int DK, int M, int CH, bool FUSED = false>
 __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &st, const KeyCodes<M ? M : 4> &kc_in,
                                              v4u (&v)[CH], const float *lut_s, __amdgpu_buffer_rsrc_t rc,
                                              __amdgpu_buffer_rsrc_t rv, int bh, uint32_t kb, uint32_t k1,
-                                             uint32_t kofs, int lane, int m, const ArgMin *enc_s = nullptr)
+                                             uint32_t kofs, int lane, int m, const double *enc_d = nullptr)
 {
     constexpr int LPR = DK / 8;
     constexpr int NLD = LPR;
@@ -282,13 +282,21 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &
 #pragma unroll
             for (int w = 0; w < (M + 3) / 4; ++w)
                 kc.w[w] = 0u;
+            const int *enc_c = reinterpret_cast<const int *>(enc_d + M * kDecWaves);
 #pragma unroll
             for (int i = 0; i < M; ++i) {
-                ArgMin best = enc_s[i * kDecWaves];
+                // waves hold ascending centroid ranges: strict '<' keeps the lowest index on ties
+                double bd = enc_d[i * kDecWaves];
+                int bc = enc_c[i * kDecWaves];
 #pragma unroll
-                for (int w = 1; w < kDecWaves; ++w)
-                    best = argmin_pick(best, enc_s[i * kDecWaves + w]);
-                kc.w[i / 4] |= (uint32_t)best.c << (8 * (i % 4));
+                for (int w = 1; w < kDecWaves; ++w) {
+                    const double d = enc_d[i * kDecWaves + w];
+                    const int c = enc_c[i * kDecWaves + w];
+                    const bool better = d < bd;
+                    bd = better ? d : bd;
+                    bc = better ? c : bc;
+                }
+                kc.w[i / 4] |= (uint32_t)bc << (8 * (i % 4));
             }
             uint8_t *dst = a.codes_w + (int64_t)bh * a.code_stride + (int64_t)key * M;
             if constexpr (M == 2) {
@@ -371,7 +379,8 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                                   // [m][256]
     float *red_s = smem + (M ? M : a.m) * kCentroids;      // [WAVES][DK + 2]
-    ArgMin *enc_s = reinterpret_cast<ArgMin *>(red_s + WAVES * (DK + 2));   // fused step: [M][WAVES]
+    double *enc_d = reinterpret_cast<double *>(red_s + WAVES * (DK + 2));   // fused step: [M][WAVES] minima,
+    int *enc_c = reinterpret_cast<int *>(enc_d + (M ? M : 1) * kDecWaves);     //             then [M][WAVES] indices
 
     int bh, split;
     if (!map_block(a, bh, split))
@@ -443,6 +452,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
         for (int i0 = 0; i0 < M; i0 += GS) {
             if (i0 > 0)
                 load_centroid_rows<DSUB, GS>(frow, cbh, i0);
+            double dv[GS], dm[GS];
 #pragma unroll
             for (int g = 0; g < GS; ++g) {
                 const int i = i0 + g;
@@ -451,9 +461,18 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
                 for (int j = 0; j < DSUB; ++j)
                     e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
                 lut_s[i * kCentroids + tid] = e;
-                const ArgMin best = argmin_wave(argmin_make(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid));
-                if (lane == 0)
-                    enc_s[i * kDecWaves + wave] = best;
+                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
+                dm[g] = dv[g];
+            }
+            dmin_wave<GS>(dm);
+#pragma unroll
+            for (int g = 0; g < GS; ++g) {
+                // lowest lane that holds the wave minimum = lowest centroid index of this wave
+                const uint64_t holders = __ballot(dv[g] == dm[g]);
+                if (lane == 0) {
+                    enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
+                    enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+                }
             }
         }
     } else {
@@ -475,12 +494,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
     // occupy the address pipeline), and a tile's registers are dead at the loop back-edge.
     SoftmaxState st;
     if (kb < k1) {
-        consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_s);
+        consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
             load_rows<DK, CH>(v, rv, kb, 0, lane);
-            consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_s);
+            consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
         }
     }
     float m_run = st.m_run, z = st.z;
@@ -698,7 +717,7 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
     dim3 block(kDecThreads);
     const size_t lds = ((size_t)a.m * kCentroids + (size_t)kDecWaves * (DK + 2)) * sizeof(float) +
-                       (size_t)a.m * kDecWaves * sizeof(ArgMin);
+                       (size_t)a.m * kDecWaves * (sizeof(double) + sizeof(int));
     switch (a.m) {
     case 2:   // 32- or 64-coordinate rows: give the register allocator the larger budget
         hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT>), grid, block, lds, st, a);

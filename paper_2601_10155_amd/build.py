@@ -15,6 +15,8 @@ OBJ_DIR = os.path.join(PKG, "_build")
 # -packed-fp32-ops off: keeps the compiler from forming packed fp32 instructions.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          # leading kernel arguments arrive in scalar registers at wave launch (no load round trip)
+          "-mllvm", "-amdgpu-kernarg-preload-count=16",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # per-file extras: the encoder's distance must not be contracted into fused multiply-adds
 EXTRA = {"encode.hip": ["-ffp-contract=off"]}

@@ -49,6 +49,59 @@ struct DecodeArgs {
     int H;
 };
 
+// Kernel parameters.  The first 14 dwords of a kernel's arguments are delivered in scalar
+// registers at wave launch (kernarg preload, -amdgpu-kernarg-preload-count); anything after
+// them costs a round trip to memory before it can be used (about a microsecond on a fresh
+// argument block, and a 52 MB decode launch lasts about ten).  So everything a wavefront needs
+// before it can request its first tile travels in those 14 dwords, as scalars, and the rest
+// follows in a struct that is read while the tile is in flight.
+struct DecodeLate {
+    float *part;
+    float *out;
+    float *scores_out;
+    const void *q;
+    const void *k_new;
+    uint8_t *codes_w;
+    int d_k;
+    int m;
+};
+#define LOOKAT_DECODE_HEAD_PARAMS                                                                              \
+    int p_BH, int p_splits, int p_H, const void *p_table, const uint8_t *p_codes, const __half *p_values,     \
+        uint32_t p_code_stride, uint32_t p_value_stride, uint32_t p_L, uint32_t p_kps, float p_scale_log2e
+#define LOOKAT_DECODE_HEAD_ARGS(a, fused)                                                                      \
+    (a).BH, (a).splits, (a).H, ((fused) ? static_cast<const void *>((a).codebooks) : static_cast<const void *>((a).lut)), \
+        (a).codes, (a).values, (uint32_t)(a).code_stride, (uint32_t)(a).value_stride, (uint32_t)(a).L,        \
+        (uint32_t)(a).keys_per_split, (a).scale_log2e
+static DecodeLate late_of(const DecodeArgs &a)
+{
+    return DecodeLate{a.part, a.out, a.scores_out, a.q, a.k_new, a.codes_w, a.d_k, a.m};
+}
+__device__ __forceinline__ DecodeArgs rebuild_args(LOOKAT_DECODE_HEAD_PARAMS, const DecodeLate &late, bool fused)
+{
+    DecodeArgs a;
+    a.lut = fused ? nullptr : static_cast<const float *>(p_table);
+    a.codebooks = fused ? static_cast<const float *>(p_table) : nullptr;
+    a.codes = p_codes;
+    a.values = p_values;
+    a.part = late.part;
+    a.out = late.out;
+    a.scores_out = late.scores_out;
+    a.code_stride = p_code_stride;
+    a.value_stride = p_value_stride;
+    a.L = p_L;
+    a.keys_per_split = p_kps;
+    a.BH = p_BH;
+    a.splits = p_splits;
+    a.d_k = late.d_k;
+    a.m = late.m;
+    a.scale_log2e = p_scale_log2e;
+    a.q = late.q;
+    a.k_new = late.k_new;
+    a.codes_w = late.codes_w;
+    a.H = p_H;
+    return a;
+}
+
 // Workgroup id -> (bh, split).  Consecutive workgroup ids land on different dies, each
 // with its own L2; this mapping keeps all splits of one (b,h) on one die so that its
 // table is fetched into a single L2.
@@ -366,8 +419,11 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
 // the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
 template <int DK, int M, int WAVES, int OCC, typename FT = void>
-__global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_DECODE_HEAD_PARAMS,
+                                                                         const DecodeLate late)
 {
+    const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
+                                      p_L, p_kps, p_scale_log2e, late, !std::is_void<FT>::value);
     constexpr bool FUSED = !std::is_void<FT>::value;
     static_assert(!FUSED || (WAVES == kDecWaves && M != 0), "fused step: 256 threads, compile-time m");
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
@@ -432,6 +488,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
     KeyCodes<M ? M : 4> kc;
     if constexpr (M != 0)
         kc.load(rc, (kb + kofs) * M);
+    __builtin_amdgcn_sched_barrier(0);   // keep the request order: codes before value rows
     v4u v[CH];
     load_rows<DK, CH>(v, rv, kb, 0, lane);
     if constexpr (FUSED) {
@@ -550,8 +607,11 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(const D
 
 // Any d_k (multiple of 8, <= 256) and any m: one 256-key tile per step, scores through LDS,
 // thread j owns output coordinate j.  Used for head dimensions without a tuned kernel.
-__global__ __launch_bounds__(kDecThreads) void decode_split_generic_kernel(const DecodeArgs a)
+__global__ __launch_bounds__(kDecThreads) void decode_split_generic_kernel(LOOKAT_DECODE_HEAD_PARAMS,
+                                                                           const DecodeLate late)
 {
+    const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
+                                      p_L, p_kps, p_scale_log2e, late, false);
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                          // [m][256]
     float *p_s = smem + a.m * kCentroids;         // [256] scores -> weights of the tile
@@ -679,19 +739,24 @@ static void launch_tuned(const DecodeArgs &a, dim3 grid, hipStream_t st)
     const size_t lds = ((size_t)a.m * kCentroids + (size_t)WAVES * (DK + 2)) * sizeof(float);
     switch (a.m) {
     case 2:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2, WAVES, OCC>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, WAVES, OCC>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
         break;
     case 4:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 4, WAVES, OCC>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, WAVES, OCC>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
         break;
     case 8:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 8, WAVES, OCC>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, WAVES, OCC>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
         break;
     case 16:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 16, WAVES, OCC>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, WAVES, OCC>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
         break;
     default:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 0, WAVES, OCC>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 0, WAVES, OCC>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
         break;
     }
 }
@@ -720,16 +785,20 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
                        (size_t)a.m * kDecWaves * (sizeof(double) + sizeof(int));
     switch (a.m) {
     case 2:   // 32- or 64-coordinate rows: give the register allocator the larger budget
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+                           late_of(a));
         return true;
     case 4:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+                           late_of(a));
         return true;
     case 8:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+                           late_of(a));
         return true;
     case 16:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT>), grid, block, lds, st, a);
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+                           late_of(a));
         return true;
     default:
         return false;
@@ -767,6 +836,8 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
         return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of m=%d bytes", shape->m);
     if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
+    if (code_stride_bh > 0xffffffffLL || value_stride_bh > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
     const int64_t BH = (int64_t)shape->B * shape->H;
     const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds;
     if (nblocks > 0x7fffffffLL)
@@ -854,6 +925,8 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     if (scores_out && (reinterpret_cast<uintptr_t>(scores_out) & 3u))
         return fail(LOOKAT_ERR_ALIGN, "scores_out must be 4-byte aligned");
 
+    if (code_stride_bh > 0xffffffffLL || value_stride_bh > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
     // kernels address one (b,h) slab with 32-bit byte offsets (plus one tile of prefetch)
     if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
@@ -922,7 +995,8 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
         }
     } else {
         const size_t lds = ((size_t)shape->m * kCentroids + kDecThreads + kDecWaves) * sizeof(float);
-        hipLaunchKernelGGL(decode_split_generic_kernel, grid, dim3(kDecThreads), lds, st, a);
+        hipLaunchKernelGGL(decode_split_generic_kernel, grid, dim3(kDecThreads), lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false),
+                           late_of(a));
     }
     if (int rc = check_launch("lookat_attend_decode (split kernel)"))
         return rc;

@@ -32,7 +32,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"],
+                    help="C1..C3: decode step (C2 is the configuration the metric is quoted on); C4: prefill block")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
@@ -83,6 +84,9 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = li.CONFIGS[args.workload]
+    if cfg.T > 1:
+        prefill_main(args, cfg, lk, li, torch, device)
+        return
     scale = 1.0 / math.sqrt(cfg.d_k)
     layers = [Layer(lk, li, cfg, device, i, args.kmeans_iters) for i in range(cfg.layers)]
     splits = lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L)
@@ -227,6 +231,82 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, layers, scale, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+def prefill_main(args, cfg, lk, li, torch, device):
+    """Prefill block (configuration C4): a step = encode the block's keys, build every query's tables
+    as a materialised array (matrix cores), score the causal block from on-chip tables.  One JSON
+    line with the step rate and one roofline entry per kernel."""
+    import numpy as np
+
+    case = li.torch_case(cfg, device, layer=0)
+    cb = lk.lookat_kmeans(case["calib"], case["cb_init"], args.kmeans_iters)
+    keys, q = case["keys"], case["q"]
+    codes = torch.empty((cfg.B, cfg.H, cfg.L, cfg.m), dtype=torch.uint8, device=device)
+    lut = torch.empty((cfg.B, cfg.H, cfg.T, cfg.m, cfg.K), dtype=torch.float32, device=device)
+    scores = torch.empty((cfg.B, cfg.H, cfg.T, cfg.L), dtype=torch.float32, device=device)
+    calls = {
+        "encode_keys": lambda: lk.lookat_encode_keys(keys, cb, codes_out=codes),
+        "build_lut": lambda: lk.lookat_build_lut(q, cb, lut_out=lut),
+        "score_prefill": lambda: lk.lookat_score_prefill(q, cb, codes, scores_out=scores),
+    }
+
+    def step():
+        for fn in calls.values():
+            fn()
+
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    us = {}
+    for name, fn in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us[name] = e0.elapsed_time(e1) * 1e3 / args.steps
+
+    BH, nk = cfg.B * cfg.H, cfg.B * cfg.H * cfg.L
+    pairs = BH * (cfg.T * (cfg.T + 1) // 2 + cfg.T * (cfg.L - cfg.T))        # visible (query, key) pairs
+    enc_ops = nk * cfg.d_k * cfg.K * 3                                          # sub, mul, add in fp64 per (key, centroid, coordinate)
+    lut_bytes = lut.numel() * 4
+    lut_flops = BH * cfg.T * cfg.d_k * cfg.K * 2
+    lds_bytes = pairs * cfg.m * 4                                               # 4 bytes of table per (query, key, subspace)
+    score_bytes = scores.numel() * 4
+    LDS_PEAK = 256 * 128 * 2.4e9 / 1e9                                          # 256 CUs x 128 B/clk x 2.4 GHz, GB/s
+    result = {
+        "metric": "LOOKAT prefill block: causal (query,key) pairs scored/sec/GPU",
+        "value": pairs * args.steps / elapsed,
+        "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} T=L={cfg.L} d_k={cfg.d_k} m={cfg.m} K={cfg.K}; "
+                               "encode_keys (fp16 keys) + build_lut (T queries per head, materialised) + score_prefill"},
+        "roofline": {"bound": "alu", "kernel": "lookat::score_prefill_kernel (LDS gather bound)",
+                     "achieved": lds_bytes / us["score_prefill"] / 1e3, "peak": LDS_PEAK, "unit": "GB/s",
+                     "frac": lds_bytes / us["score_prefill"] / 1e3 / LDS_PEAK, "traffic": None,
+                     "us_per_launch": us["score_prefill"], "scores_written_GBs": score_bytes / us["score_prefill"] / 1e3},
+        "kernels": {
+            "encode_kernel": {"bound": "alu", "us": us["encode_keys"], "achieved": enc_ops / us["encode_keys"] / 1e6,
+                              "peak": 39.3, "unit": "T fp64 op/s (no FMA: half of 78.6 TFLOP/s)",
+                              "frac": enc_ops / us["encode_keys"] / 1e6 / 39.3},
+            "build_lut_mfma_kernel": {"bound": "hbm", "us": us["build_lut"], "achieved": lut_bytes / us["build_lut"] / 1e3,
+                                      "peak": HBM_PEAK_GBS, "unit": "GB/s (table written)",
+                                      "frac": lut_bytes / us["build_lut"] / 1e3 / HBM_PEAK_GBS,
+                                      "mfma_TFLOPs": lut_flops / us["build_lut"] / 1e6, "mfma_peak_fp32_TFLOPs": 157.3},
+        },
+    }
     print(json.dumps(result), flush=True)
 
 

@@ -47,6 +47,8 @@ struct PrefillArgs {
     int T;
     int H;
     int tiles;                // ceil(T / 4)
+    int BH;
+    int groups;               // ceil(tiles / kPfGroup)
 };
 
 template <int M>
@@ -73,7 +75,7 @@ struct PfCodes {
     __device__ __forceinline__ uint32_t byte(int i) const { return (w[i / 4] >> (8 * (i % 4))) & 0xffu; }
 };
 
-// grid = (ceil(tiles / kPfGroup), BH); heavy (late) tiles are dispatched first.
+// grid = 8 * ceil(BH / 8) * ceil(tiles / kPfGroup) workgroups, mapped to ((b,h), tile group) below.
 template <typename QT, int DK, int M>
 __global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const PrefillArgs a)
 {
@@ -86,7 +88,17 @@ __global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const Pref
     float *lut_s = smem;                      // [M][256][TQ]
     float *q_s = smem + PAIRS * TQ;           // [TQ][DK]
 
-    const int bh = blockIdx.y;
+    // Workgroup ids are dealt round-robin to the 8 dies, each with its own 4 MB L2.  (b,h) pairs
+    // are assigned so that a die only ever sees the heads congruent to its index mod 8: its L2
+    // then holds a few heads' codebooks (128 KB each at d_k = 128) instead of cycling through all
+    // of them.  Within a die, late (long) tile groups come first.
+    const int xcd = blockIdx.x % 8;
+    const int slot = blockIdx.x / 8;
+    const int bh_per_xcd = (a.BH + 7) / 8;
+    const int bh = (slot % bh_per_xcd) * 8 + xcd;
+    const int group = a.groups - 1 - slot / bh_per_xcd;
+    if (bh >= a.BH)
+        return;
     const int h = bh % a.H;
     const int tid = threadIdx.x;
     const int64_t off = a.L - a.T;            // query t sits at position t + off
@@ -112,7 +124,6 @@ __global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const Pref
         }
     }
 
-    const int group = (int)(gridDim.x - 1 - blockIdx.x);   // late tiles first
     for (int g = 0; g < kPfGroup; ++g) {
         const int tile = group * kPfGroup + (kPfGroup - 1 - g);
         if (tile >= a.tiles)
@@ -214,7 +225,9 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
             configured = true;
         }
     }
-    dim3 grid((unsigned)((a.tiles + kPfGroup - 1) / kPfGroup), (unsigned)BH);
+    a.BH = BH;
+    a.groups = (a.tiles + kPfGroup - 1) / kPfGroup;
+    dim3 grid((unsigned)((BH + 7) / 8 * 8 * a.groups));
     hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);
     return check_launch("lookat_score_prefill");
 }
@@ -262,8 +275,12 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
     const int cvec = (shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16) ? shape->m : 1;
     if ((reinterpret_cast<uintptr_t>(codes) % cvec) || (code_stride_bh % cvec))
         return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of %d bytes for m=%d", cvec, shape->m);
-    if ((int64_t)shape->B * shape->H > 65535)
-        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H=%lld exceeds one launch", (long long)shape->B * shape->H);
+    {
+        const int64_t BHp = ((int64_t)shape->B * shape->H + 7) / 8 * 8;
+        const int64_t groups = ((int64_t)(T + kPfTQ - 1) / kPfTQ + kPfGroup - 1) / kPfGroup;
+        if (BHp * groups > 0x7fffffffLL)
+            return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*T=%lld*%d exceeds one launch", (long long)shape->B * shape->H, T);
+    }
     PrefillArgs a;
     a.q = q;
     a.codebooks = codebooks;
@@ -274,6 +291,8 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
     a.T = T;
     a.H = shape->H;
     a.tiles = 0;
+    a.BH = 0;
+    a.groups = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
     return (q_dtype == LOOKAT_F16) ? dispatch_prefill<__half>(shape, a, st) : dispatch_prefill<float>(shape, a, st);
 }

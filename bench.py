@@ -2,14 +2,19 @@
 """LOOKAT decode benchmark on one MI355X.
 
 A "step" is one pass of the decode hot path over every layer of the workload: per layer,
-encode the new token's key into the code cache (lookat_encode_keys), build the query's
-lookup tables (lookat_build_lut), attend over the coded cache (lookat_attend_decode).
+encode the new token's key into the code cache, build the query's lookup tables, attend over
+the coded cache.  `--path fused` (the default where the shape has a fused instance) does the
+three in ONE kernel per layer (lookat_decode_step); `--path calls` makes the three library
+calls (lookat_encode_keys, lookat_build_lut, lookat_attend_decode).  The step is captured in a
+HIP graph (`--mode graph`, default) and every replay is compared with the eager result.
 Inputs are seeded and synthetic (lookat_inputs), resident in HBM before the timed region;
 codebooks come from the library's own Lloyd iterations on seeded calibration keys.
+`--workload C4` times the prefill block instead (encode, table build, causal scoring).
 
 Prints ONE JSON line: whole-step throughput in keys scored per second, the HBM roofline
 of the decode kernel (algorithmic code+value bytes / average launch duration, measured
-with HIP events on the launch stream) and the CPU oracle timed on a bounded sample.
+with HIP events on the launch stream, plus counted HBM traffic) and the CPU oracle timed on a
+bounded sample.
 """
 from __future__ import annotations
 
@@ -25,6 +30,26 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+# HBM traffic per launch of the dominant kernel, from hardware counters (they cannot be read
+# inside this process: two separate `rocprofv3 --pmc` runs of this script, FETCH_SIZE then
+# WRITE_SIZE, recorded under profiles/*_hbm_counters.md).  Entry: (FETCH_SIZE per dispatch,
+# FETCH_SIZE of lookat::stream_read_kernel in the same run, KiB that kernel reads, WRITE_SIZE
+# per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
+COUNTED_TRAFFIC = {
+    ("C1", True): (1239.01, 778.004, 1536.0, 3.375),
+    ("C1", False): (831.504, 778.004, 1536.0, 3.0),
+    ("C2", True): (26382.5, 24586.0, 49152.0, 108.0),
+    ("C2", False): (26151.5, 24586.0, 49152.0, 96.0),
+    ("C3", False): (1.08262e6, 1.04859e6, 2097152.0, 268.278),
+}
+
+
+def counted_traffic(key):
+    if key not in COUNTED_TRAFFIC:
+        return None
+    fetch, stream_fetch, known_kib, write_kib = COUNTED_TRAFFIC[key]
+    return int(round((fetch * known_kib / stream_fetch + write_kib) * 1024.0))
 
 
 def parse_args():
@@ -61,7 +86,6 @@ class Layer:
         self.q = case["q"]
         self.lut = torch.empty((cfg.B, cfg.H, 1, cfg.m, cfg.K), dtype=torch.float32, device=device)
         self.out = torch.empty((cfg.B, cfg.H, cfg.d_k), dtype=torch.float32, device=device)
-        self.host_keys_last = None
         del case
 
 
@@ -218,7 +242,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": counted_traffic((cfg.name, fused)),
             "bytes_per_launch": bytes_per_launch,
             "us_per_launch": us_per_launch,
             "launches_timed": n_launch,

@@ -5,30 +5,41 @@
 //     scores[b,h,t,l] = sum_i LUT_{b,h,t,i}[codes[b,h,l,i]]   for l <= t + (L - T),  else -inf.
 //
 // Shape of the computation on gfx950
-//   * one workgroup (512 threads) = one (b,h) and kPfGroup consecutive tiles of TQ = 4 queries;
-//     two workgroups fit a compute unit (64 KB of tables each), so one builds tables on the
-//     vector ALU while the other gathers from LDS;
+//   * one workgroup (256 threads = 4 wavefronts) = one (b,h) and kPfGroup consecutive tiles of
+//     TQ = 4 queries; two workgroups fit a compute unit (64 KB of tables each at m = 16), so one
+//     builds tables on the matrix cores while the other gathers from LDS.  Two wavefronts per SIMD
+//     leave each 256 registers: thread c keeps centroid c of EVERY subspace (d_k floats) for all
+//     the workgroup's tiles, so a tile's tables cost no codebook traffic and nothing spills;
 //   * the tables of a tile live in LDS as lut_s[i][c][4] (fp32): the four queries' entries of one
 //     (subspace, centroid) are adjacent, so ONE 16-byte LDS read per (key, subspace) serves four
-//     queries.  Against a [query][i][c] layout with 4-byte gathers this is a quarter of the LDS
-//     instructions, and the 16-byte stride spreads a pass of 8 lanes over all banks;
-//   * the head's codebook is held in registers across the workgroup's tiles (thread p owns the
-//     (subspace, centroid) pairs p, p+512, ...), so a tile's tables cost d_sub FMAs per entry and
-//     no codebook traffic.  With 4 queries per tile the contraction is 4 wide: a 32x32 or 16x16
-//     MFMA tile would be 75-87% padding and fp32 MFMA has no rate advantage over the vector
-//     ALU, so this step stays on the vector ALU;
-//   * the scoring loop is bound by LDS read bandwidth (4 bytes per (query, key, subspace)) and by
-//     the scores written (4 bytes per (query, key)).
+//     queries: a quarter of the gather instructions of a [query][i][c] layout;
+//   * table build: per subspace the product [4 queries x d_sub] . [d_sub x 256 centroids] is done
+//     with v_mfma_f32_4x4x1 (16 independent 4x4 outer products per instruction, fp32 in and out).
+//     A = the four queries' coordinate j (lane%4 picks the query, the same in every block),
+//     B = coordinate j of the lane's own centroid, so after d_sub instructions lane c holds the
+//     four queries' entries for centroid c: exactly one 16-byte LDS store.  On the vector ALU the
+//     same build costs 4 FMAs and an LDS operand read per (centroid, coordinate) and was 60% of
+//     the kernel's LDS instructions;
+//   * the scoring loop is bound by LDS gather bandwidth (4 bytes per (query, key, subspace)) and by
+//     the scores written to HBM (4 bytes per (query, key), masked ones included).  The gathers hit
+//     random bank groups: an LDS read of 16 bytes per lane is served 8 lanes at a time and 8 random
+//     codes pile 2.7 deep on average (measured 21.8 cycles per gather instruction instead of 8).
+//     A conflict-free variant was built and measured: tables as [i/8][c][i%8][4] with lane l
+//     walking the subspaces in the order (u + l) % 8, which needs the 8 accumulators of a lane
+//     rotated by c%8 before they are stored.  It cut the conflict cycles by 70% and was 45% slower
+//     (the rotation's selects and the extra registers cost more than the conflicts), as was keeping
+//     a thread's codes in registers across tiles; neither is kept.
 #include "common.h"
 
 namespace lookat {
 
-constexpr int kPfThreads = 512;
+constexpr int kPfThreads = 256;   // = centroids per subspace: thread c owns centroid c
 constexpr int kPfTQ = 4;      // queries per tile
 constexpr int kPfGroup = 8;   // query tiles per workgroup (codebook registers reused)
 
 typedef unsigned int pf_v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int pf_v2u __attribute__((ext_vector_type(2)));
+typedef float pf_v4f __attribute__((ext_vector_type(4)));
 
 template <typename QT>
 __device__ __forceinline__ float pf_to_f32(QT v);
@@ -75,18 +86,41 @@ struct PfCodes {
     __device__ __forceinline__ uint32_t byte(int i) const { return (w[i / 4] >> (8 * (i % 4))) & 0xffu; }
 };
 
+// Sum of the four queries' table entries of one key over all subspaces, ascending subspace order
+// (as Algorithm 1 sums), GB gathers requested before the first is used.  Tables as [i][c][4].
+template <int M>
+__device__ __forceinline__ pf_v4f pf_score_key(const float *lut_s, const PfCodes<M> &kc)
+{
+    constexpr int GB = M < 4 ? M : 4;
+    pf_v4f s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i0 = 0; i0 < M; i0 += GB) {
+        pf_v4f v[GB];
+#pragma unroll
+        for (int u = 0; u < GB; ++u)
+            v[u] = *reinterpret_cast<const pf_v4f *>(lut_s + ((i0 + u) * kCentroids + kc.byte(i0 + u)) * kPfTQ);
+#pragma unroll
+        for (int u = 0; u < GB; ++u)
+            s += v[u];
+    }
+    return s;
+}
+
 // grid = 8 * ceil(BH / 8) * ceil(tiles / kPfGroup) workgroups, mapped to ((b,h), tile group) below.
 template <typename QT, int DK, int M>
-__global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const PrefillArgs a)
+__global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const PrefillArgs a)
 {
     constexpr int TQ = kPfTQ;
+    constexpr int NT = kPfThreads;
     constexpr int DSUB = DK / M;
-    constexpr int PAIRS = M * kCentroids;                          // (subspace, centroid) pairs
-    constexpr int PP = (PAIRS + kPfThreads - 1) / kPfThreads;      // pairs per thread
-    constexpr int GB = M < 4 ? M : 4;                              // gathers in flight per key
+    constexpr int QE = TQ * DK / NT;               // query elements staged per thread and tile
+    constexpr int QS = DK + 4;                     // row stride of q_s in floats
+    static_assert(NT == kCentroids, "thread c owns centroid c");
+    static_assert(DSUB % 4 == 0 && M % 2 == 0 && (TQ * DK) % NT == 0, "operand reads are 16 bytes wide");
     extern __shared__ __align__(16) float smem[];
-    float *lut_s = smem;                      // [M][256][TQ]
-    float *q_s = smem + PAIRS * TQ;           // [TQ][DK]
+    float *lut_s = smem;                           // [M][256][TQ]
+    float *q_s = smem + M * kCentroids * TQ;       // [2][TQ][QS]: rows 16 bytes apart modulo the 128-byte bank row
+    pf_v4f *lut4 = reinterpret_cast<pf_v4f *>(lut_s);
 
     // Workgroup ids are dealt round-robin to the 8 dies, each with its own 4 MB L2.  (b,h) pairs
     // are assigned so that a die only ever sees the heads congruent to its index mod 8: its L2
@@ -105,103 +139,123 @@ __global__ __launch_bounds__(kPfThreads, 4) void score_prefill_kernel(const Pref
     const QT *qg = static_cast<const QT *>(a.q) + (int64_t)bh * a.T * DK;
     const uint8_t *codes_bh = a.codes + (int64_t)bh * a.code_stride;
     float *scores_bh = a.scores + (int64_t)bh * a.T * a.L;
-
-    // codebook rows of this thread's (subspace, centroid) pairs, kept for all tiles
-    float row[PP][DSUB];
+    // centroid `tid` of every subspace, kept for all tiles of the workgroup
+    float row[M][DSUB];
 #pragma unroll
-    for (int k = 0; k < PP; ++k) {
-        const int p = tid + k * kPfThreads;
-        if (p < PAIRS) {
-            const float4 *src = reinterpret_cast<const float4 *>(a.codebooks + ((int64_t)h * PAIRS + p) * DSUB);
+    for (int i = 0; i < M; ++i) {
+        const float4 *src =
+            reinterpret_cast<const float4 *>(a.codebooks + (((int64_t)h * M + i) * kCentroids + tid) * DSUB);
 #pragma unroll
-            for (int j4 = 0; j4 < DSUB / 4; ++j4) {
-                const float4 v = src[j4];
-                row[k][4 * j4] = v.x;
-                row[k][4 * j4 + 1] = v.y;
-                row[k][4 * j4 + 2] = v.z;
-                row[k][4 * j4 + 3] = v.w;
-            }
+        for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+            const float4 v = src[j4];
+            row[i][4 * j4] = v.x;
+            row[i][4 * j4 + 1] = v.y;
+            row[i][4 * j4 + 2] = v.z;
+            row[i][4 * j4 + 3] = v.w;
         }
     }
 
-    for (int g = 0; g < kPfGroup; ++g) {
-        const int tile = group * kPfGroup + (kPfGroup - 1 - g);
-        if (tile >= a.tiles)
-            continue;
+    const int tile_lo = group * kPfGroup;
+    const int tile_hi = (tile_lo + kPfGroup - 1 < a.tiles) ? tile_lo + kPfGroup - 1 : a.tiles - 1;
+    float qreg[QE];   // a tile's query elements on their way from HBM to LDS
+    auto fetch_q = [&](int tile) {
+#pragma unroll
+        for (int e = 0; e < QE; ++e) {
+            const int x = tid + e * NT;
+            const int t = tile * TQ + x / DK;
+            qreg[e] = (t < a.T) ? pf_to_f32<QT>(qg[(int64_t)t * DK + x % DK]) : 0.f;
+        }
+    };
+    auto stage_q = [&](float *dst) {
+#pragma unroll
+        for (int e = 0; e < QE; ++e) {
+            const int x = tid + e * NT;
+            dst[(x / DK) * QS + x % DK] = qreg[e];
+        }
+    };
+    fetch_q(tile_hi);
+    stage_q(q_s);
+    int cur = 0;
+
+    for (int tile = tile_hi; tile >= tile_lo; --tile) {
         const int t0 = tile * TQ;
         const int64_t vis_last = t0 + TQ - 1 + off;                     // last key any query of the tile sees
-        const int64_t kmax = (vis_last + 1 < a.L) ? vis_last + 1 : a.L;
+        const int kmax = (int)((vis_last + 1 < a.L) ? vis_last + 1 : a.L);
+        const float *q_lane = q_s + cur * (TQ * QS) + (tid & 3) * QS;   // matrix operand: query (lane % 4) of the tile
 
-        __syncthreads();   // the previous tile's readers are done with lut_s / q_s
-        for (int e = tid; e < TQ * DK; e += kPfThreads) {
-            const int t = t0 + e / DK;
-            q_s[e] = (t < a.T) ? pf_to_f32<QT>(qg[(int64_t)t * DK + e % DK]) : 0.f;
-        }
-        // codes of this thread's first key: requested now, needed after the table build
-        PfCodes<M> kc;
+        __syncthreads();   // this tile's queries are staged; the previous tile's readers are done with lut_s
+        // The next tile's queries are requested now and written to the other half of q_s after the
+        // build: by then the previous tile's score stores, which that wait also covers, have drained.
+        if (tile > tile_lo)
+            fetch_q(tile - 1);
+        // codes of this thread's first two keys: requested now, needed after the build
+        PfCodes<M> kc0, kc1;
         if (tid < kmax)
-            kc.load(codes_bh + (int64_t)tid * M);
-        __syncthreads();
+            kc0.load(codes_bh + (int64_t)tid * M);
+        if (tid + NT < kmax)
+            kc1.load(codes_bh + (int64_t)(tid + NT) * M);
 
-        // ---- tables of the tile: lut_s[(i*256 + c)*4 + t] = q[t]^(i) . C_i[c], j ascending ----
+        // ---- tables as [i][c][4]: lut4[i*256 + c] = (q[t]^(i) . C_i[c])_{t=0..3}, j ascending ----
+        // Two subspaces at a time: their accumulator chains are independent, so one chain's
+        // matrix-core latency is covered by the other's instruction.
 #pragma unroll
-        for (int k = 0; k < PP; ++k) {
-            const int p = tid + k * kPfThreads;
-            if (p < PAIRS) {
-                const int i = p / kCentroids;   // uniform over the wavefront: q_s reads are broadcasts
-                float acc[TQ];
+        for (int i = 0; i < M; i += 2) {
+            pf_v4f acc0 = {0.f, 0.f, 0.f, 0.f};
+            pf_v4f acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < TQ; ++t) {
-                    const float4 *qv = reinterpret_cast<const float4 *>(q_s + t * DK + i * DSUB);
-                    acc[t] = 0.f;
+            for (int j4 = 0; j4 < DSUB / 4; ++j4) {
+                const pf_v4f x0 = *reinterpret_cast<const pf_v4f *>(q_lane + i * DSUB + 4 * j4);
+                const pf_v4f x1 = *reinterpret_cast<const pf_v4f *>(q_lane + (i + 1) * DSUB + 4 * j4);
 #pragma unroll
-                    for (int j4 = 0; j4 < DSUB / 4; ++j4) {
-                        const float4 x = qv[j4];
-                        acc[t] = fmaf(x.x, row[k][4 * j4], acc[t]);
-                        acc[t] = fmaf(x.y, row[k][4 * j4 + 1], acc[t]);
-                        acc[t] = fmaf(x.z, row[k][4 * j4 + 2], acc[t]);
-                        acc[t] = fmaf(x.w, row[k][4 * j4 + 3], acc[t]);
-                    }
+                for (int u = 0; u < 4; ++u) {
+                    acc0 = __builtin_amdgcn_mfma_f32_4x4x1f32(x0[u], row[i][4 * j4 + u], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_4x4x1f32(x1[u], row[i + 1][4 * j4 + u], acc1, 0, 0, 0);
                 }
-                *reinterpret_cast<float4 *>(lut_s + (int64_t)p * TQ) = make_float4(acc[0], acc[1], acc[2], acc[3]);
             }
+            lut4[i * kCentroids + tid] = acc0;
+            lut4[(i + 1) * kCentroids + tid] = acc1;
         }
+        if (tile > tile_lo)
+            stage_q(q_s + (cur ^ 1) * (TQ * QS));
+        cur ^= 1;
         __syncthreads();
 
-        // ---- scoring: one key per thread and step, four scores per key ----
-        for (int64_t l = tid; l < kmax; l += kPfThreads) {
-            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        // ---- scoring: two keys per thread and step, four scores per key ----
+        // score rows of the tile: uniform bases (scalar registers) indexed by the 32-bit key number
+        float *rowp[TQ];
 #pragma unroll
-            for (int i0 = 0; i0 < M; i0 += GB) {
-                float4 v[GB];
-#pragma unroll
-                for (int u = 0; u < GB; ++u)
-                    v[u] = *reinterpret_cast<const float4 *>(lut_s + ((i0 + u) * kCentroids + kc.byte(i0 + u)) * TQ);
-#pragma unroll
-                for (int u = 0; u < GB; ++u) {   // ascending subspace order, as Algorithm 1 sums
-                    s.x += v[u].x;
-                    s.y += v[u].y;
-                    s.z += v[u].z;
-                    s.w += v[u].w;
-                }
-            }
-            const int64_t ln = l + kPfThreads;
-            if (ln < kmax)
-                kc.load(codes_bh + ln * M);   // next key of this thread
-            const float sv[TQ] = {s.x, s.y, s.z, s.w};
+        for (int t = 0; t < TQ; ++t)
+            rowp[t] = scores_bh + (int64_t)(t0 + t) * a.L;
+        auto put = [&](int l, const pf_v4f &sc) {
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 const int tq = t0 + t;
                 if (tq < a.T)
-                    scores_bh[(int64_t)tq * a.L + l] = (l <= tq + off) ? sv[t] : -INFINITY;
+                    rowp[t][(uint32_t)l] = (l <= tq + off) ? sc[t] : -INFINITY;
             }
+        };
+        for (int l = tid; l < kmax; l += 2 * NT) {
+            const int l1 = l + NT;
+            const bool has1 = l1 < kmax;
+            const pf_v4f s0 = pf_score_key<M>(lut_s, kc0);
+            pf_v4f s1 = {0.f, 0.f, 0.f, 0.f};
+            if (has1)
+                s1 = pf_score_key<M>(lut_s, kc1);
+            const int n0 = l + 2 * NT, n1 = l1 + 2 * NT;
+            if (n0 < kmax)
+                kc0.load(codes_bh + (int64_t)n0 * M);   // next keys of this thread
+            if (n1 < kmax)
+                kc1.load(codes_bh + (int64_t)n1 * M);
+            put(l, s0);
+            if (has1)
+                put(l1, s1);
         }
         // ---- keys no query of the tile may see ----
         for (int t = 0; t < TQ; ++t) {
             const int tq = t0 + t;
             if (tq >= a.T)
                 break;
-            for (int64_t l = kmax + tid; l < a.L; l += kPfThreads)
+            for (int64_t l = kmax + tid; l < a.L; l += NT)
                 scores_bh[(int64_t)tq * a.L + l] = -INFINITY;
         }
     }
@@ -212,7 +266,7 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
 {
     PrefillArgs a = a0;
     a.tiles = (a.T + kPfTQ - 1) / kPfTQ;
-    const size_t lds = ((size_t)M * kCentroids * kPfTQ + (size_t)kPfTQ * DK) * sizeof(float);
+    const size_t lds = ((size_t)M * kCentroids * kPfTQ + 2 * (size_t)kPfTQ * (DK + 4)) * sizeof(float);
     auto kern = score_prefill_kernel<QT, DK, M>;
     if (lds > 64 * 1024) {
         static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS

@@ -139,12 +139,12 @@ def test_config_c4_full_size_prefill(lk):
         got = _slab(scores, b, h)
         vis = np.isfinite(ref)
         assert np.array_equal(np.isneginf(got), ~vis)
-        # summand magnitude sum_i |LUT_i[c_i]| per (t, l)
-        T, L = ref.shape[2], ref.shape[3]
-        mag = np.zeros((1, 1, T, L))
-        for i in range(cfg.m):
-            idx = np.broadcast_to(codes_ref[0, 0, None, :, i].astype(np.int64), (T, L))
-            mag[0, 0] += np.take_along_axis(np.abs(lut_ref[0, 0, :, i, :].astype(np.float64)), idx, axis=-1)
+        # summand magnitude sum_i sum_j |q_j| |C_i[c_i]_j| per (t, l): the tables are built in the kernel
+        d_sub = cfg.d_k // cfg.m
+        qa = np.abs(_slab(case["q"], b, h).astype(np.float64)).reshape(cfg.T, cfg.m, d_sub)
+        picked = np.stack([np.abs(cbn[h, i].astype(np.float64))[codes_ref[0, 0, :, i].astype(np.int64)]
+                           for i in range(cfg.m)], axis=1)                           # [L, m, d_sub]
+        mag = np.einsum("tid,lid->tl", qa, picked)[None, None]
         err = np.abs(np.where(vis, got, 0.0) - np.where(vis, ref, 0.0))
         assert np.all(err <= REL * np.maximum(mag, 1e-6)), f"max err {err.max()}"
         # the materialised tables of the same queries (matrix-core path) agree with the oracle's

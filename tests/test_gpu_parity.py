@@ -326,23 +326,23 @@ def _prefill_check(lk, case, cb, codes):
     vis = np.isfinite(ref)
     assert np.array_equal(np.isneginf(got), ~vis), "mask differs"
     B, H, T, m, K = lut_ref.shape
-    L = codes.shape[2]
-    # tolerance relative to sum_i |LUT_i[c_i]| per (t, l)
-    mag = np.zeros((B, H, T, L))
-    for i in range(m):
-        tab = np.abs(lut_ref[:, :, :, i, :].astype(np.float64))                      # [B,H,T,K]
-        idx = np.broadcast_to(codes[:, :, None, :, i].astype(np.int64), (B, H, T, L))
-        mag += np.take_along_axis(tab, idx, axis=-1)
+    # The tables are built inside the kernel, so a score's summands are the products q_j * c_j of
+    # every subspace: tolerance relative to sum_i sum_j |q_j| |C_i[c_i]_j| per (t, l).
+    d_sub = cb.shape[3]
+    qa = np.abs(q.astype(np.float64)).reshape(B, H, T, m, d_sub)
+    picked = np.stack([np.abs(cb.astype(np.float64))[np.arange(H)[None, :, None], i, codes[:, :, :, i].astype(np.int64)]
+                       for i in range(m)], axis=3)                                   # [B,H,L,m,d_sub]
+    mag = np.einsum("bhtid,bhlid->bhtl", qa, picked)
     err = np.abs(got[vis].astype(np.float64) - ref[vis].astype(np.float64))
     assert np.all(err <= REL * np.maximum(mag[vis], 1e-6)), f"max err {err.max()}"
 
 
 @pytest.mark.parametrize("d_k,m", [(128, 16), (128, 8), (64, 4), (64, 2), (64, 16)])
 @pytest.mark.parametrize("q_dtype", ["float16", "float32"])
-@pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0)])
+@pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135)])
 def test_score_prefill_parity(lk, d_k, m, q_dtype, T, extra):
     """Ragged query tiles (T not a multiple of 8 or 32), queries that are the tail of a longer
-    cache (extra > 0), a single query."""
+    cache (extra > 0), a single query, a block whose late tiles take several 256-key steps."""
     L = T + extra
     cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)
     case = li.make_case(cfg, seed=5000 + d_k + m + T)

@@ -19,7 +19,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
           "-mllvm", "-amdgpu-kernarg-preload-count=16",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 # per-file extras: the encoder's distance must not be contracted into fused multiply-adds
-EXTRA = {"encode.hip": ["-ffp-contract=off"]}
+EXTRA = {"encode.hip": ["-ffp-contract=off"], "encode_filter.hip": ["-ffp-contract=off"]}
 
 
 def hipcc() -> str:

@@ -5,6 +5,8 @@
 //
 // This translation unit must be compiled with -ffp-contract=off: a fused multiply-add
 // in the distance would change near-tie decisions.
+#include <cstdlib>
+
 #include "common.h"
 
 #pragma clang fp contract(off)
@@ -270,6 +272,10 @@ static void launch_encode(const lookat_shape *s, int64_t N, const void *keys, co
 #undef LOOKAT_ENC_CASE
 }
 
+// encode_filter.hip: matrix-core filter in front of the exact rule (d_sub in {4, 8, 16, 32})
+bool launch_encode_filter(const lookat_shape *s, int64_t N, const void *keys, int key_dtype, const float *codebooks,
+                          uint8_t *codes, int64_t code_stride_bh, hipStream_t st);
+
 }  // namespace lookat
 
 extern "C" int lookat_encode_keys(const lookat_shape *shape, int64_t N, const void *keys, int key_dtype,
@@ -301,7 +307,13 @@ extern "C" int lookat_encode_keys(const lookat_shape *shape, int64_t N, const vo
     // thread-per-key grid reaches a few workgroups per compute unit.
     const int64_t per_key_blocks = (rows + kEncThreads - 1) / kEncThreads * shape->m * shape->H;
     bool done = false;
-    if (per_key_blocks < 1024 && (rows + kEncFewKeys - 1) / kEncFewKeys <= 0x7fffffffLL) {
+    // From a few 32-key blocks per head upwards the filter kernel is the fast path; the environment
+    // variable LOOKAT_ENCODE_EXACT=1 forces the plain exact kernels (same codes, for comparison runs).
+    const char *exact_env = getenv("LOOKAT_ENCODE_EXACT");
+    const bool exact_only = exact_env && exact_env[0] == '1';
+    if (!exact_only && rows >= 64)
+        done = launch_encode_filter(shape, N, keys, key_dtype, codebooks, codes, code_stride_bh, st);
+    if (!done && per_key_blocks < 1024 && (rows + kEncFewKeys - 1) / kEncFewKeys <= 0x7fffffffLL) {
         done = (key_dtype == LOOKAT_F16)
                    ? launch_encode_few<__half>(shape, N, keys, codebooks, codes, code_stride_bh, st)
                    : launch_encode_few<float>(shape, N, keys, codebooks, codes, code_stride_bh, st);

@@ -114,6 +114,46 @@ def test_encode_ties_and_duplicates(lk, n_keys):
     assert (got[:, 0, 10:20, 1] == 5).all()
 
 
+@pytest.mark.parametrize("d_k,m", [(64, 4), (128, 16), (64, 16), (64, 2)])
+@pytest.mark.parametrize("key_dtype", ["float32", "float16"])
+def test_encode_near_ties_sweep(lk, d_k, m, key_dtype):
+    """Keys placed on the bisector of two centroids and pushed off it by 1e-9 .. 1e-2 of the
+    centroid distance, towards either side: the fp32 filter in front of the exact rule must hand
+    every case it cannot decide to the exact rule, whatever the size of the push."""
+    d_sub = d_k // m
+    rng = np.random.default_rng(77 + d_k + m)
+    H, B, N = 2, 2, 4096
+    cb = (rng.standard_normal((H, m, 256, d_sub)) * 2).astype(np.float32)
+    keys = (rng.standard_normal((B, H, N, d_k)) * 2).astype(np.float32)
+    for b in range(B):
+        for h in range(H):
+            for n in range(0, N, 2):            # every other key is a constructed near tie
+                i = int(rng.integers(m))
+                ca, cc = rng.choice(256, 2, replace=False)
+                mid = 0.5 * (cb[h, i, ca].astype(np.float64) + cb[h, i, cc])
+                dirn = cb[h, i, ca].astype(np.float64) - cb[h, i, cc]
+                eps = 10.0 ** rng.uniform(-9, -2) * rng.choice([-1.0, 1.0])
+                keys[b, h, n, i * d_sub:(i + 1) * d_sub] = (mid + eps * dirn).astype(np.float32)
+    keys = keys.astype(key_dtype)
+    ref = oracle.encode_keys(keys, cb)
+    got = lk.lookat_encode_keys(dev(keys), dev(cb)).cpu().numpy()
+    assert np.array_equal(got, ref), f"{(got != ref).sum()} of {ref.size} codes differ"
+
+
+def test_encode_filter_and_exact_kernels_agree(lk, monkeypatch):
+    """The filter kernel and the plain exact kernels (forced through the environment switch) give
+    the same codes, both equal to the oracle's."""
+    cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=3000, T=1, n_calib=512)
+    case = li.make_case(cfg, seed=1700)
+    cb, _ = oracle.kmeans(case["calib"], case["cb_init"], 1)
+    ref = oracle.encode_keys(case["keys"], cb)
+    fast = lk.lookat_encode_keys(dev(case["keys"]), dev(cb)).cpu().numpy()
+    monkeypatch.setenv("LOOKAT_ENCODE_EXACT", "1")
+    slow = lk.lookat_encode_keys(dev(case["keys"]), dev(cb)).cpu().numpy()
+    monkeypatch.delenv("LOOKAT_ENCODE_EXACT")
+    assert np.array_equal(fast, ref) and np.array_equal(slow, ref)
+
+
 def test_encode_append_into_cache(lk):
     cfg = li.shrink(li.CONFIGS["C2"], B=2, H=3, L=5, n_calib=300)
     case = li.make_case(cfg, seed=5)

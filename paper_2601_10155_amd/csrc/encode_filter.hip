@@ -31,6 +31,8 @@
 // denormals; an infinite or NaN S sends the key to the exact rule.
 //
 // This translation unit must be compiled with -ffp-contract=off (the exact rule).
+#include <cstdlib>
+
 #include "common.h"
 
 #pragma clang fp contract(off)
@@ -78,41 +80,48 @@ __device__ __forceinline__ uint64_t ef_order_key(double d, int c)
 // The exact rule for key `l` of the block (l uniform over the wavefront), all 64 lanes working:
 // lanes 0..31 accumulate coordinates 0..DSUB/2-1 of their 8 centroids and hand the partial sums to
 // lanes 32..63, which add the remaining coordinates: one chain per centroid, coordinates ascending.
-// Rare path: operands are re-read from memory in rolled loops, so it holds no registers.
+// Operands are re-read from memory (the matrix fragments are scaled and split), a few centroid
+// rows at a time so that the loads of a batch are in flight together.
 template <typename KT, int DSUB>
 __device__ __forceinline__ int ef_exact_code(const KT *key_sub, const float *cb, int col, int h2)
 {
     constexpr int DH = DSUB / 2;
-    const KT *xsrc = key_sub + h2 * DH;
+    constexpr int TB = (32 / DH) > 8 ? 8 : (32 / DH);   // centroid rows per batch: at most 32 registers of operands
+    KT xr[DH];
+    ef_load<KT, DH>(key_sub + h2 * DH, xr);
     uint64_t okey = ~0ull;
     int oc = kCentroids;
 #pragma unroll 1
-    for (int t = 0; t < 8; ++t) {
-        const float *csrc = cb + (int64_t)(32 * t + col) * DSUB + h2 * DH;
-        double part = 0.0;
-        if (!h2) {
-#pragma unroll 1
+    for (int t0 = 0; t0 < 8; t0 += TB) {
+        float cr[TB][DH];
+#pragma unroll
+        for (int u = 0; u < TB; ++u)
+            ef_load<float, DH>(cb + (int64_t)(32 * (t0 + u) + col) * DSUB + h2 * DH, cr[u]);
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            double part = 0.0;
+#pragma unroll
             for (int mm = 0; mm < DH; ++mm) {
-                const double diff = (double)ef_to_f32<KT>(xsrc[mm]) - (double)csrc[mm];
+                const double diff = (double)ef_to_f32<KT>(xr[mm]) - (double)cr[u][mm];
                 const double sq = diff * diff;
                 part = part + sq;
             }
-        }
-        const unsigned long long bits = (unsigned long long)__double_as_longlong(part);
-        const unsigned long long from_lo = __shfl_xor(bits, 32);   // upper lanes receive the lower half's sum
-        if (h2) {
+            // upper lanes restart from the lower half's sum: (lower sum) + their coordinates, in order
+            const unsigned long long from_lo = __shfl_xor((unsigned long long)__double_as_longlong(part), 32);
             double acc = __longlong_as_double((long long)from_lo);
-#pragma unroll 1
+#pragma unroll
             for (int mm = 0; mm < DH; ++mm) {
-                const double diff = (double)ef_to_f32<KT>(xsrc[mm]) - (double)csrc[mm];
+                const double diff = (double)ef_to_f32<KT>(xr[mm]) - (double)cr[u][mm];
                 const double sq = diff * diff;
                 acc = acc + sq;
             }
-            const int c = 32 * t + col;
-            const uint64_t k2 = ef_order_key(acc, c);
-            if (k2 < okey) {   // c ascends with t: strict '<' keeps the lowest index
-                okey = k2;
-                oc = c;
+            if (h2) {
+                const int c = 32 * (t0 + u) + col;
+                const uint64_t k2 = ef_order_key(acc, c);
+                if (k2 < okey) {   // c ascends with t: strict '<' keeps the lowest index
+                    okey = k2;
+                    oc = c;
+                }
             }
         }
     }
@@ -370,9 +379,10 @@ __global__ __launch_bounds__(kEfThreads, 2) void encode_filter_kernel(const KT *
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float x = acc_cur[r];
-                idx = (x < best) ? (32 * t + 8 * (r / 4) + (r % 4)) : idx;   // + 4*h2, added below
-                second = __builtin_amdgcn_fmed3f(best, x, second);          // best <= second: the middle one
-                best = __builtin_amdgcn_fmed3f(best, x, -INFINITY);         // = min(best, x), one instruction
+                const bool lt = x < best;
+                idx = lt ? (32 * t + 8 * (r / 4) + (r % 4)) : idx;   // + 4*h2, added below
+                second = __builtin_amdgcn_fmed3f(best, x, second);  // best <= second: the middle one
+                best = lt ? x : best;   // a select on the same compare: fminf would add a NaN-quieting instruction
             }
             if (t < 7) {
                 // NI groups of (1 matrix instruction, 64/NI vector instructions)
@@ -423,7 +433,8 @@ static bool launch_encode_filter_t(const lookat_shape *s, int64_t N, const void 
     const int64_t total_blocks = (int64_t)s->B * blocks_per_bh;
     // enough workgroups to fill the chip several times over, and at least 8 key blocks per wavefront
     // so that loading the codebook (the price of a wavefront) is amortised
-    int64_t splits = (2048 + (int64_t)s->H * s->m - 1) / ((int64_t)s->H * s->m);
+    static const int64_t target_wgs = getenv("LOOKAT_EF_WGS") ? atoi(getenv("LOOKAT_EF_WGS")) : 2048;
+    int64_t splits = (target_wgs + (int64_t)s->H * s->m - 1) / ((int64_t)s->H * s->m);
     const int64_t by_work = (total_blocks + kEfWaves * 8 - 1) / (kEfWaves * 8);
     if (splits > by_work)
         splits = by_work;

@@ -42,6 +42,7 @@ COUNTED_TRAFFIC = {
     ("C2", True): (26382.5, 24586.0, 49152.0, 108.0),
     ("C2", False): (26151.5, 24586.0, 49152.0, 96.0),
     ("C3", False): (1.08262e6, 1.04859e6, 2097152.0, 268.278),
+    ("C4", "score_prefill"): (89775.5, 1.0, 2.0, 2.09942e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
 
@@ -308,6 +309,9 @@ def prefill_main(args, cfg, lk, li, torch, device):
     lds_bytes = pairs * cfg.m * 4                                               # 4 bytes of table per (query, key, subspace)
     score_bytes = scores.numel() * 4
     LDS_PEAK = 256 * 128 * 2.4e9 / 1e9                                          # 256 CUs x 128 B/clk x 2.4 GHz, GB/s
+    VALU_PEAK = 256 * 4 * 16 * 2.4e9 / 1e12                                     # single-operation fp32 lane-instructions, T/s
+    cand = nk * cfg.m * cfg.K                                                   # candidates ranked by the encoder's filter
+    d_sub = cfg.d_k // cfg.m
     result = {
         "metric": "LOOKAT prefill block: causal (query,key) pairs scored/sec/GPU",
         "value": pairs * args.steps / elapsed,
@@ -319,12 +323,18 @@ def prefill_main(args, cfg, lk, li, torch, device):
                                "encode_keys (fp16 keys) + build_lut (T queries per head, materialised) + score_prefill"},
         "roofline": {"bound": "alu", "kernel": "lookat::score_prefill_kernel (LDS gather bound)",
                      "achieved": lds_bytes / us["score_prefill"] / 1e3, "peak": LDS_PEAK, "unit": "GB/s",
-                     "frac": lds_bytes / us["score_prefill"] / 1e3 / LDS_PEAK, "traffic": None,
+                     "frac": lds_bytes / us["score_prefill"] / 1e3 / LDS_PEAK,
+                     "traffic": counted_traffic((cfg.name, "score_prefill")),
                      "us_per_launch": us["score_prefill"], "scores_written_GBs": score_bytes / us["score_prefill"] / 1e3},
         "kernels": {
-            "encode_kernel": {"bound": "alu", "us": us["encode_keys"], "achieved": enc_ops / us["encode_keys"] / 1e6,
-                              "peak": 39.3, "unit": "T fp64 op/s (no FMA: half of 78.6 TFLOP/s)",
-                              "frac": enc_ops / us["encode_keys"] / 1e6 / 39.3},
+            "encode_filter_kernel": {"bound": "alu", "us": us["encode_keys"],
+                                     "achieved": cand * 4 / us["encode_keys"] / 1e6, "peak": VALU_PEAK,
+                                     "unit": "T lane-instructions/s (4 vector instructions per (key, subspace, centroid) "
+                                             "candidate: compare, two selects, median; peak 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz)",
+                                     "frac": cand * 4 / us["encode_keys"] / 1e6 / VALU_PEAK,
+                                     "mfma_TFLOPs": cand * d_sub * 4 / us["encode_keys"] / 1e6,
+                                     "mfma_peak_fp16_TFLOPs": 2500.0,
+                                     "exact_fp64_scan_equivalent_Top_s": enc_ops / us["encode_keys"] / 1e6},
             "build_lut_mfma_kernel": {"bound": "hbm", "us": us["build_lut"], "achieved": lut_bytes / us["build_lut"] / 1e3,
                                       "peak": HBM_PEAK_GBS, "unit": "GB/s (table written)",
                                       "frac": lut_bytes / us["build_lut"] / 1e3 / HBM_PEAK_GBS,

@@ -139,6 +139,36 @@ int lookat_attend_decode(const lookat_shape *shape, int64_t L,
                          void *stream);
 
 /*
+ * Attention decode with grouped queries (the combination with grouped-query attention that the
+ * paper names as future work, Sec. "Future Work"; sharing of key/value heads: Sec. "Structural
+ * Approaches"): `group` consecutive query heads share one key/value head.  Per query head the
+ * computation is Algorithm 1 unchanged,
+ *     s[b,hq,l]   = sum_i lut[b,hq,i, codes[b, hq/group, l, i]]
+ *     out[b,hq,:] = sum_l softmax_l(scale * s[b,hq,:]) * values[b, hq/group, l, :]
+ * but the codes and values of a key/value head are streamed once for its `group` query heads.
+ *
+ *   shape           B, H = number of KEY/VALUE heads, d_k, m, K; query heads = H * group
+ *   group           1, 2, 4 or 8 (1 forwards to lookat_attend_decode)
+ *   lut             [B, H*group, m, K] fp32, 16-byte aligned (tables of query head hq built against
+ *                   the codebooks of key/value head hq/group)
+ *   codes, values   as in lookat_attend_decode, indexed by key/value head
+ *   out             [B, H*group, d_k] fp32;  scores_out: [B, H*group, L] fp32 or NULL
+ *   workspace       lookat_attend_decode_gqa_workspace_bytes(shape, group, L, num_splits) bytes
+ * Supported: d_k in {64, 128}, m in {2, 4, 8, 16}, group*m tables within the 160 KB of LDS;
+ * otherwise LOOKAT_ERR_UNSUPPORTED.  Other rules (ownership, stream, errors) as lookat_attend_decode.
+ */
+size_t lookat_attend_decode_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L, int32_t num_splits);
+
+int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group, int64_t L,
+                             const float *lut,
+                             const uint8_t *codes, int64_t code_stride_bh,
+                             const void *values, int64_t value_stride_bh,
+                             float scale, int32_t num_splits,
+                             void *workspace, size_t workspace_bytes,
+                             float *out, float *scores_out,
+                             void *stream);
+
+/*
  * Fused decode step: the three calls a decode step makes per layer, in one kernel.
  * For every (b,h):
  *   1. the new token's key k_new[b,h,:] is encoded by the rule of lookat_encode_keys and its m

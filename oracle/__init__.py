@@ -45,6 +45,7 @@ def _load():
         lib.oracle_build_lut.argtypes = [i32, i32, i32, i32, i32, i32, vp, i32, vp, vp]
         lib.oracle_adc_scores.argtypes = [i32, i32, i64, i32, i32, vp, vp, vp]
         lib.oracle_attend_decode.argtypes = [i32, i32, i64, i32, i32, i32, vp, vp, vp, dbl, vp, vp, vp]
+        lib.oracle_attend_decode_gqa.argtypes = [i32, i32, i32, i64, i32, i32, i32, vp, vp, vp, dbl, vp, vp]
         lib.oracle_score_prefill.argtypes = [i32, i32, i32, i64, i32, i32, vp, vp, vp]
         lib.oracle_decode_codes.argtypes = [i32, i32, i64, i32, i32, i32, vp, vp, vp]
         lib.oracle_dense_attention.argtypes = [i32, i32, i64, i32, vp, i32, vp, vp, dbl, vp]
@@ -140,6 +141,24 @@ def attend_decode(lut, codes, values, scale, want_scores=False, want_alpha=False
     if want_alpha:
         res.append(a)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+def attend_decode_gqa(lut, codes, values, scale, want_scores=False):
+    """Grouped queries: lut [B,H*g,m,K], codes [B,H,L,m], values [B,H,L,d_k] fp16 -> out [B,H*g,d_k]
+    fp32 (and the unscaled scores [B,H*g,L]); query head hq reads key/value head hq // g."""
+    lut = np.ascontiguousarray(lut, dtype=np.float32)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    values = np.ascontiguousarray(values)
+    assert values.dtype == np.float16
+    B, HQ, m, K = lut.shape
+    H, L, d_k = values.shape[1], values.shape[2], values.shape[3]
+    assert HQ % H == 0 and codes.shape == (B, H, L, m) and values.shape[0] == B
+    g = HQ // H
+    out = np.empty((B, HQ, d_k), dtype=np.float32)
+    s = np.empty((B, HQ, L), dtype=np.float32) if want_scores else None
+    _check(_load().oracle_attend_decode_gqa(B, H, g, L, d_k, m, K, _ptr(lut), _ptr(codes), _ptr(values),
+                                            float(scale), _ptr(out), _ptr(s)), "attend_decode_gqa")
+    return (out, s) if want_scores else out
 
 
 def score_prefill(lut, codes):

@@ -235,6 +235,68 @@ int oracle_attend_decode(int B, int H, int64_t L, int d_k, int m, int K,
     return rc;
 }
 
+/* Grouped queries (the paper's "Future Work": LOOKAT combined with grouped-query attention;
+ * key/value sharing across heads: "Structural Approaches").  `group` consecutive query heads share
+ * one key/value head; per query head hq the computation is Algorithm 1 unchanged, with the codes
+ * and values of key/value head hq / group:
+ *   lut [B, H*group, m, K], codes [B, H, L, m], values [B, H, L, d_k]  ->  out [B, H*group, d_k],
+ *   scores_out [B, H*group, L] (may be NULL). */
+int oracle_attend_decode_gqa(int B, int H, int group, int64_t L, int d_k, int m, int K,
+                             const float *lut, const uint8_t *codes,
+                             const uint16_t *values, double scale,
+                             float *out, float *scores_out)
+{
+    if (L <= 0 || group <= 0)
+        return -2;
+    int HQ = H * group;
+    int64_t BHQ = (int64_t)B * HQ;
+    int rc = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t bq = 0; bq < BHQ; ++bq) {
+        int64_t b = bq / HQ;
+        int hq = (int)(bq % HQ);
+        int64_t kv = b * H + hq / group;            /* the key/value head this query head reads */
+        const float *t = lut + bq * m * K;
+        double *s = (double *)malloc(sizeof(double) * (size_t)L);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d_k);
+        if (!s || !o) {
+            rc = -8;
+            free(s);
+            free(o);
+            continue;
+        }
+        for (int64_t l = 0; l < L; ++l) {
+            double raw = adc_score(t, codes + (kv * L + l) * m, m, K);
+            if (scores_out)
+                scores_out[bq * L + l] = (float)raw;
+            s[l] = scale * raw;
+        }
+        double mx = s[0];
+        for (int64_t l = 1; l < L; ++l)
+            if (s[l] > mx)
+                mx = s[l];
+        double z = 0.0;
+        for (int64_t l = 0; l < L; ++l) {
+            s[l] = exp(s[l] - mx);
+            z = z + s[l];
+        }
+        for (int j = 0; j < d_k; ++j)
+            o[j] = 0.0;
+        for (int64_t l = 0; l < L; ++l) {
+            double a = s[l] / z;
+            const uint16_t *v = values + (kv * L + l) * d_k;
+            for (int j = 0; j < d_k; ++j)
+                o[j] = o[j] + a * half_bits_to_double(v[j]);
+        }
+        for (int j = 0; j < d_k; ++j)
+            out[bq * d_k + j] = (float)o[j];
+        free(s);
+        free(o);
+    }
+    return rc;
+}
+
+
 /* Prefill form of the lookup-and-sum: the T queries of a block are the last T positions
  * of a cache of L >= T keys, so query t sits at position t + (L - T) and scores the keys
  * l <= t + (L - T) (causal, self included; for L == T: l <= t).  Entries it may not see are

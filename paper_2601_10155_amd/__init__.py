@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     lookat_attend_decode,
+    lookat_attend_decode_gqa,
     lookat_build_lut,
     lookat_decode_step,
     lookat_encode_keys,
@@ -29,6 +30,6 @@ from .binding import (  # noqa: F401
 __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
-    "lookat_attend_decode", "lookat_build_lut", "lookat_decode_step", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
+    "lookat_attend_decode", "lookat_attend_decode_gqa", "lookat_build_lut", "lookat_decode_step", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
     "lookat_probe_stream_read", "lookat_score_prefill",
 ]

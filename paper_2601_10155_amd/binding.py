@@ -54,6 +54,10 @@ def load_library():
         lib.lookat_attend_decode_auto_splits.restype = i32
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_attend_decode_gqa_workspace_bytes.argtypes = [sp, i32, i64, i32]
+        lib.lookat_attend_decode_gqa_workspace_bytes.restype = sz
+        lib.lookat_attend_decode_gqa.argtypes = [sp, i32, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
+        lib.lookat_attend_decode_gqa.restype = ctypes.c_int
         lib.lookat_decode_step.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, vp, vp]
         lib.lookat_decode_step.restype = ctypes.c_int
         lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
@@ -214,6 +218,43 @@ def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.T
                                     values.data_ptr(), vs, float(scale), int(num_splits), ws_ptr, ws_bytes,
                                     out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
                                     _stream(values)))
+    return out
+
+
+def lookat_attend_decode_gqa(lut: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,
+                             num_splits: int = 0, workspace: torch.Tensor | None = None,
+                             out: torch.Tensor | None = None, scores_out: torch.Tensor | None = None) -> torch.Tensor:
+    """Grouped queries: lut [B,H*g,m,256] fp32, codes [B,H,L,m] u8, values [B,H,L,d_k] fp16
+    -> out [B,H*g,d_k] fp32; H counts key/value heads, g = lut.shape[1] // H query heads share each."""
+    lib = load_library()
+    _dev(lut, "lut"), _dev(codes, "codes"), _dev(values, "values")
+    B, H, L, m = codes.shape
+    d_k = values.shape[3]
+    if lut.dim() != 4 or lut.shape[0] != B or lut.shape[1] % H or tuple(lut.shape[2:]) != (m, 256) \
+            or lut.dtype != torch.float32 or not lut.is_contiguous():
+        raise ValueError("lut must be contiguous fp32 [B,H*g,m,256]")
+    g = lut.shape[1] // H
+    if codes.dtype != torch.uint8 or values.dtype != torch.float16 or tuple(values.shape[:3]) != (B, H, L):
+        raise ValueError("codes must be uint8 [B,H,L,m] and values fp16 [B,H,L,d_k]")
+    shape = _Shape(B, H, d_k, m, 256)
+    cs = _bh_stride(codes, "codes")
+    vs = _bh_stride(values, "values")
+    need = int(lib.lookat_attend_decode_gqa_workspace_bytes(ctypes.byref(shape), g, L, num_splits))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+    if out is None:
+        out = torch.empty((B, H * g, d_k), dtype=torch.float32, device=values.device)
+    if out.dtype != torch.float32 or out.numel() != B * H * g * d_k or not out.is_contiguous():
+        raise ValueError("out must be contiguous fp32 [B,H*g,d_k]")
+    if scores_out is not None and (scores_out.dtype != torch.float32 or scores_out.numel() != B * H * g * L
+                                   or not scores_out.is_contiguous()):
+        raise ValueError("scores_out must be contiguous fp32 [B,H*g,L]")
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.lookat_attend_decode_gqa(ctypes.byref(shape), g, L, lut.data_ptr(), codes.data_ptr(), cs,
+                                        values.data_ptr(), vs, float(scale), int(num_splits), ws_ptr, ws_bytes,
+                                        out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
+                                        _stream(values)))
     return out
 
 

@@ -308,18 +308,31 @@ __device__ __forceinline__ void dmin_wave(double (&x)[N])
     }
 }
 
-// Online-softmax state of one wavefront (base-2 exponent domain).
+// Online-softmax state of one wavefront (base-2 exponent domain), for each of the G query heads
+// that share the key/value head (G = 1: plain multi-head attention).
+template <int G>
 struct SoftmaxState {
-    float m_run = -INFINITY;   // running max of scale*log2e*s over the keys seen so far
-    float z = 0.f;             // this lane's share of the running sum of weights
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // this lane's slice of sum_l w_l v_l
+    float m_run[G];    // running max of scale*log2e*s over the keys seen so far
+    float z[G];        // this lane's share of the running sum of weights
+    float acc[G][8];   // this lane's slice of sum_l w_l v_l
+    __device__ __forceinline__ SoftmaxState()
+    {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            m_run[g] = -INFINITY;
+            z[g] = 0.f;
+#pragma unroll
+            for (int d = 0; d < 8; ++d)
+                acc[g][d] = 0.f;
+        }
+    }
 };
 
 // One 64-key tile of a wavefront: its codes (kc) and first CH value-row groups (v) are in
 // registers or in flight.  Scores one key per lane (key = kb + kofs), updates the running
 // max / sum, and accumulates the weighted value rows.
-template <int DK, int M, int CH, bool FUSED = false>
-__device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &st, const KeyCodes<M ? M : 4> &kc_in,
+template <int DK, int M, int CH, bool FUSED = false, int G = 1>
+__device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G> &st, const KeyCodes<M ? M : 4> &kc_in,
                                              v4u (&v)[CH], const float *lut_s, __amdgpu_buffer_rsrc_t rc,
                                              __amdgpu_buffer_rsrc_t rv, int bh, uint32_t kb, uint32_t k1,
                                              uint32_t kofs, int lane, int m, const double *enc_d = nullptr)
@@ -361,29 +374,36 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState &
             }
         }
     }
-    float raw;
-    if constexpr (M != 0)
-        raw = kc.score(lut_s);
-    else
-        raw = score_bytes(lut_s, rc, key * m, m);
-    float s = -INFINITY;
-    if (key < k1) {
-        if (a.scores_out)
-            a.scores_out[(int64_t)bh * a.L + key] = raw;
-        s = raw * a.scale_log2e;
-    }
-    const float m_new = fmaxf(st.m_run, wave_max(s));
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float corr = fast_exp2(st.m_run - m_use);
-    const float p = fast_exp2(s - m_use);
-    st.z = st.z * corr + p;
+    // one score per query head of the group: the same codes index that head's tables
+    float p[G];
 #pragma unroll
-    for (int d = 0; d < 8; ++d)
-        st.acc[d] *= corr;
-    st.m_run = m_new;
+    for (int g = 0; g < G; ++g) {
+        float raw;
+        if constexpr (M != 0)
+            raw = kc.score(lut_s + g * (M * kCentroids));
+        else
+            raw = score_bytes(lut_s + g * (m * kCentroids), rc, key * m, m);
+        float s = -INFINITY;
+        if (key < k1) {
+            if (a.scores_out)
+                a.scores_out[((int64_t)bh * G + g) * a.L + key] = raw;
+            s = raw * a.scale_log2e;
+        }
+        const float m_new = fmaxf(st.m_run[g], wave_max(s));
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = fast_exp2(st.m_run[g] - m_use);
+        p[g] = fast_exp2(s - m_use);
+        st.z[g] = st.z[g] * corr + p[g];
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+            st.acc[g][d] *= corr;
+        st.m_run[g] = m_new;
+    }
 #pragma unroll
     for (int c0 = 0; c0 < NLD; c0 += CH) {
-        fma_rows<LPR, CH>(st.acc, p, v, c0);
+#pragma unroll
+        for (int g = 0; g < G; ++g)   // the value rows are read once and weighted G times
+            fma_rows<LPR, CH>(st.acc[g], p[g], v, c0);
         if (c0 + CH < NLD)
             load_rows<DK, CH>(v, rv, kb, c0 + CH, lane);   // next row groups of this tile
     }
@@ -418,14 +438,17 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused
 // decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
 // the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
-template <int DK, int M, int WAVES, int OCC, typename FT = void>
+// G > 1: grouped-query attention: the workgroup's (b,h) is a KEY/VALUE head shared by G query heads,
+// whose tables (contiguous in memory) are all staged in LDS; codes and values are streamed once.
+template <int DK, int M, int WAVES, int OCC, typename FT = void, int G = 1>
 __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_DECODE_HEAD_PARAMS,
                                                                          const DecodeLate late)
 {
     const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
                                       p_L, p_kps, p_scale_log2e, late, !std::is_void<FT>::value);
     constexpr bool FUSED = !std::is_void<FT>::value;
-    static_assert(!FUSED || (WAVES == kDecWaves && M != 0), "fused step: 256 threads, compile-time m");
+    static_assert(!FUSED || (WAVES == kDecWaves && M != 0 && G == 1), "fused step: 256 threads, compile-time m, one query head");
+    static_assert(G == 1 || M != 0, "grouped queries: compile-time m");
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
     constexpr int RPL = kWave / LPR;       // value rows covered by one wave-wide load
     constexpr int NLD = kTile / RPL;       // wave-wide loads per tile (= LPR)
@@ -433,9 +456,9 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     constexpr int NT = WAVES * kWave;
 
     extern __shared__ __align__(16) float smem[];
-    float *lut_s = smem;                                   // [m][256]
-    float *red_s = smem + (M ? M : a.m) * kCentroids;      // [WAVES][DK + 2]
-    double *enc_d = reinterpret_cast<double *>(red_s + WAVES * (DK + 2));   // fused step: [M][WAVES] minima,
+    float *lut_s = smem;                                   // [G][m][256]
+    float *red_s = smem + G * (M ? M : a.m) * kCentroids;  // [WAVES][G][DK + 2]
+    double *enc_d = reinterpret_cast<double *>(red_s + WAVES * G * (DK + 2));   // fused step: [M][WAVES] minima,
     int *enc_c = reinterpret_cast<int *>(enc_d + (M ? M : 1) * kDecWaves);     //             then [M][WAVES] indices
 
     int bh, split;
@@ -455,13 +478,21 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     // order it is needed (loads return in order, so each wait below covers only what precedes):
     // 1) this thread's slice of the table (staged through registers: the wait before the
     //    barrier then covers the table alone, not the value rows behind it);
-    const float4 *lut_g = reinterpret_cast<const float4 *>(a.lut + (int64_t)bh * m * kCentroids);
-    constexpr int kLutRegs = M ? (M * (kCentroids / 4) + NT - 1) / NT : 1;
-    float4 lut_r[kLutRegs];
-    if constexpr (M != 0 && !FUSED) {
+    const float4 *lut_g = reinterpret_cast<const float4 *>(a.lut + (int64_t)bh * G * m * kCentroids);
+    constexpr int kLutRegs = M ? (G * M * (kCentroids / 4) + NT - 1) / NT : 1;
+    // (tables of more than one 16-byte piece per thread are copied up front instead: a staging
+    // array of several registers ends up in scratch memory)
+    constexpr bool STAGED = (M != 0 && !FUSED && kLutRegs == 1);
+    float4 lut_r[STAGED ? kLutRegs : 1];
+    if constexpr (M != 0 && !FUSED && !STAGED) {
+        float4 *s4 = reinterpret_cast<float4 *>(lut_s);
+        for (int x = tid; x < G * M * (kCentroids / 4); x += NT)
+            s4[x] = lut_g[x];
+    }
+    if constexpr (STAGED) {
 #pragma unroll
         for (int x = 0; x < kLutRegs; ++x)
-            if ((x + 1) * NT <= M * (kCentroids / 4) || tid + x * NT < M * (kCentroids / 4))
+            if ((x + 1) * NT <= G * M * (kCentroids / 4) || tid + x * NT < G * M * (kCentroids / 4))
                 lut_r[x] = lut_g[tid + x * NT];
             else
                 lut_r[x] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -534,12 +565,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
         }
     } else {
         float4 *s4 = reinterpret_cast<float4 *>(lut_s);
-        if constexpr (M != 0) {
+        if constexpr (STAGED) {
 #pragma unroll
             for (int x = 0; x < kLutRegs; ++x)
-                if ((x + 1) * NT <= M * (kCentroids / 4) || tid + x * NT < M * (kCentroids / 4))
+                if ((x + 1) * NT <= G * M * (kCentroids / 4) || tid + x * NT < G * M * (kCentroids / 4))
                     s4[tid + x * NT] = lut_r[x];
-        } else {
+        } else if constexpr (M == 0) {
             for (int x = tid; x < m * (kCentroids / 4); x += NT)
                 s4[x] = lut_g[x];
         }
@@ -549,55 +580,57 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     // First tile (requested above), then the wave's remaining tiles: request, consume.  Tiles
     // are requested only if they exist (a load past the range would return zero but still
     // occupy the address pipeline), and a tile's registers are dead at the loop back-edge.
-    SoftmaxState st;
+    SoftmaxState<G> st;
     if (kb < k1) {
-        consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+        consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
             load_rows<DK, CH>(v, rv, kb, 0, lane);
-            consume_tile<DK, M, CH, FUSED>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+            consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
         }
     }
-    float m_run = st.m_run, z = st.z;
-    float(&acc)[8] = st.acc;
 
     // ---- fold the rows of the wave, then the waves of the workgroup ----
 #pragma unroll
-    for (int d = 0; d < 8; ++d)
-        acc[d] = sum_over_lane_classes<LPR>(acc[d]);
-    z = wave_sum(z);
-    float *mine = red_s + wave * (DK + 2);
-    if (lane < LPR) {
+    for (int g = 0; g < G; ++g) {
 #pragma unroll
         for (int d = 0; d < 8; ++d)
-            mine[sub * 8 + d] = acc[d];
-    }
-    if (lane == 0) {
-        mine[DK] = m_run;
-        mine[DK + 1] = z;
+            st.acc[g][d] = sum_over_lane_classes<LPR>(st.acc[g][d]);
+        st.z[g] = wave_sum(st.z[g]);
+        float *mine = red_s + (wave * G + g) * (DK + 2);
+        if (lane < LPR) {
+#pragma unroll
+            for (int d = 0; d < 8; ++d)
+                mine[sub * 8 + d] = st.acc[g][d];
+        }
+        if (lane == 0) {
+            mine[DK] = st.m_run[g];
+            mine[DK + 1] = st.z[g];
+        }
     }
     __syncthreads();
 
-    if (tid < DK) {
+    for (int x = tid; x < G * DK; x += NT) {   // (query head of the group, output coordinate)
+        const int g = x / DK, j = x % DK;
         float mx = -INFINITY;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w)
-            mx = fmaxf(mx, red_s[w * (DK + 2) + DK]);
+            mx = fmaxf(mx, red_s[(w * G + g) * (DK + 2) + DK]);
         const float m_use = (mx == -INFINITY) ? 0.f : mx;
         float o = 0.f, zz = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) {
-            const float wgt = fast_exp2(red_s[w * (DK + 2) + DK] - m_use);
-            o = fmaf(wgt, red_s[w * (DK + 2) + tid], o);
-            zz = fmaf(wgt, red_s[w * (DK + 2) + DK + 1], zz);
+            const float wgt = fast_exp2(red_s[(w * G + g) * (DK + 2) + DK] - m_use);
+            o = fmaf(wgt, red_s[(w * G + g) * (DK + 2) + j], o);
+            zz = fmaf(wgt, red_s[(w * G + g) * (DK + 2) + DK + 1], zz);
         }
         if (a.splits == 1) {
-            a.out[(int64_t)bh * DK + tid] = o / zz;
+            a.out[((int64_t)bh * G + g) * DK + j] = o / zz;
         } else {
-            float *dst = a.part + ((int64_t)bh * a.splits + split) * (DK + 2);
-            dst[tid] = o;
-            if (tid == 0) {
+            float *dst = a.part + (((int64_t)bh * G + g) * a.splits + split) * (DK + 2);
+            dst[j] = o;
+            if (j == 0) {
                 dst[DK] = mx;
                 dst[DK + 1] = zz;
             }
@@ -805,6 +838,55 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
     }
 }
 
+// Grouped queries: 256-thread workgroups, two wavefronts per SIMD (G accumulator sets per lane).
+template <int DK, int G>
+static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    dim3 block(kDecThreads);
+    const size_t lds = ((size_t)G * a.m * kCentroids + (size_t)kDecWaves * G * (DK + 2)) * sizeof(float);
+#define LOOKAT_GQA_CASE(M_)                                                                                    \
+    case M_: {                                                                                                 \
+        auto kern = decode_split_kernel<DK, M_, kDecWaves, 2, void, G>;                                        \
+        if (lds > 64 * 1024) {                                                                                 \
+            static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
+            if (!configured) {                                                                                 \
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                      \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
+                if (e != hipSuccess)                                                                           \
+                    return fail(LOOKAT_ERR_HIP, "lookat_attend_decode_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
+                                hipGetErrorString(e));                                                         \
+                configured = true;                                                                             \
+            }                                                                                                  \
+        }                                                                                                      \
+        hipLaunchKernelGGL(kern, grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false), late_of(a));         \
+        return LOOKAT_OK;                                                                                      \
+    }
+    switch (a.m) {
+        LOOKAT_GQA_CASE(2)
+        LOOKAT_GQA_CASE(4)
+        LOOKAT_GQA_CASE(8)
+        LOOKAT_GQA_CASE(16)
+    default:
+        return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_attend_decode_gqa handles m in {2,4,8,16}; got m=%d", a.m);
+    }
+#undef LOOKAT_GQA_CASE
+}
+
+template <int DK>
+static int launch_gqa_dk(int group, const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    switch (group) {
+    case 2:
+        return launch_gqa<DK, 2>(a, grid, st);
+    case 4:
+        return launch_gqa<DK, 4>(a, grid, st);
+    case 8:
+        return launch_gqa<DK, 8>(a, grid, st);
+    default:
+        return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_attend_decode_gqa handles group in {1,2,4,8}; got %d", group);
+    }
+}
+
 }  // namespace lookat
 
 extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
@@ -1004,6 +1086,111 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
         hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)BH), dim3(kDecThreads), 0, st,
                            static_cast<const float *>(workspace), out, S, shape->d_k);
         return check_launch("lookat_attend_decode (combine kernel)");
+    }
+    return LOOKAT_OK;
+}
+
+extern "C" size_t lookat_attend_decode_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L,
+                                                           int32_t num_splits)
+{
+    using namespace lookat;
+    clear_error();
+    if (check_shape(shape) != LOOKAT_OK || L <= 0 || num_splits < 0 || group < 1)
+        return 0;
+    const int S = num_splits ? num_splits : auto_splits(shape, L);
+    if (S == 1)
+        return 0;
+    return (size_t)shape->B * shape->H * group * S * (shape->d_k + 2) * sizeof(float);
+}
+
+extern "C" int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group, int64_t L, const float *lut,
+                                        const uint8_t *codes, int64_t code_stride_bh, const void *values,
+                                        int64_t value_stride_bh, float scale, int32_t num_splits, void *workspace,
+                                        size_t workspace_bytes, float *out, float *scores_out, void *stream)
+{
+    using namespace lookat;
+    if (group == 1)
+        return lookat_attend_decode(shape, L, lut, codes, code_stride_bh, values, value_stride_bh, scale, num_splits,
+                                    workspace, workspace_bytes, out, scores_out, stream);
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (group != 2 && group != 4 && group != 8)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "group=%d: query heads per key/value head must be 1, 2, 4 or 8", group);
+    if (L <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
+    if (num_splits < 0 || num_splits > 65535)
+        return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
+    if (!lut || !codes || !values || !out)
+        return fail(LOOKAT_ERR_NULL, "lut, codes, values and out must be non-NULL");
+    if (code_stride_bh < L * shape->m || value_stride_bh < L * shape->d_k)
+        return fail(LOOKAT_ERR_SHAPE, "code_stride_bh=%lld / value_stride_bh=%lld smaller than one (b,h) slab",
+                    (long long)code_stride_bh, (long long)value_stride_bh);
+    if (!aligned16(lut) || !aligned16(values) || !aligned16(out) || ((value_stride_bh * 2) % 16))
+        return fail(LOOKAT_ERR_ALIGN, "lut, values, out and value_stride_bh must be 16-byte aligned");
+    const bool m_ok = shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16;
+    if (!m_ok || (shape->d_k != 64 && shape->d_k != 128))
+        return fail(LOOKAT_ERR_UNSUPPORTED,
+                    "lookat_attend_decode_gqa handles d_k in {64,128} with m in {2,4,8,16}; got d_k=%d m=%d", shape->d_k,
+                    shape->m);
+    if ((reinterpret_cast<uintptr_t>(codes) % shape->m) || (code_stride_bh % shape->m))
+        return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of m=%d bytes", shape->m);
+    if (scores_out && (reinterpret_cast<uintptr_t>(scores_out) & 3u))
+        return fail(LOOKAT_ERR_ALIGN, "scores_out must be 4-byte aligned");
+    if (code_stride_bh > 0xffffffffLL || value_stride_bh > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
+    if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
+    const size_t lds = ((size_t)group * shape->m * kCentroids + (size_t)kDecWaves * group * (shape->d_k + 2)) * sizeof(float);
+    if (lds > 160 * 1024)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "group=%d x m=%d tables (%zu bytes with the reduction buffer) exceed the 160 KB of LDS",
+                    group, shape->m, lds);
+    const int64_t BH = (int64_t)shape->B * shape->H;   // key/value heads
+    const int S = num_splits ? num_splits : auto_splits(shape, L);
+    const size_t need = (S == 1) ? 0 : (size_t)BH * group * S * (shape->d_k + 2) * sizeof(float);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(LOOKAT_ERR_WORKSPACE, "workspace of %zu bytes needed for %d splits, got %zu", need, S,
+                        workspace_bytes);
+        if (!aligned16(workspace))
+            return fail(LOOKAT_ERR_ALIGN, "workspace must be 16-byte aligned");
+    }
+    const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds * S;
+    if (nblocks > 0x7fffffffLL || BH * group > 0x7fffffffLL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*num_splits=%lld workgroups exceed one launch", (long long)nblocks);
+
+    DecodeArgs a;
+    a.lut = lut;
+    a.codes = codes;
+    a.values = static_cast<const __half *>(values);
+    a.part = static_cast<float *>(workspace);
+    a.out = out;
+    a.scores_out = scores_out;
+    a.code_stride = code_stride_bh;
+    a.value_stride = value_stride_bh;
+    a.L = L;
+    a.keys_per_split = round_up((L + S - 1) / S, kTile);
+    a.BH = (int)BH;
+    a.splits = S;
+    a.d_k = shape->d_k;
+    a.m = shape->m;
+    a.scale_log2e = scale * kLog2e;
+    a.q = nullptr;
+    a.k_new = nullptr;
+    a.codebooks = nullptr;
+    a.codes_w = nullptr;
+    a.H = shape->H;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)nblocks);
+    const int rc = (shape->d_k == 64) ? launch_gqa_dk<64>(group, a, grid, st) : launch_gqa_dk<128>(group, a, grid, st);
+    if (rc != LOOKAT_OK)
+        return rc;
+    if (int rc2 = check_launch("lookat_attend_decode_gqa (split kernel)"))
+        return rc2;
+    if (S > 1) {
+        hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)(BH * group)), dim3(kDecThreads), 0, st,
+                           static_cast<const float *>(workspace), out, S, shape->d_k);
+        return check_launch("lookat_attend_decode_gqa (combine kernel)");
     }
     return LOOKAT_OK;
 }

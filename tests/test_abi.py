@@ -31,7 +31,8 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
-            "lookat_probe_stream_read", "lookat_score_prefill", "lookat_decode_step"} <= set(names)
+            "lookat_probe_stream_read", "lookat_score_prefill", "lookat_decode_step",
+            "lookat_attend_decode_gqa", "lookat_attend_decode_gqa_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -162,3 +163,26 @@ def test_decode_step_argument_errors(lib):
     bad = Shape(2, 3, 32, 4, 256)
     a = list(base); a[0] = ctypes.byref(bad); a[9] = L * 32
     assert f(*a) == E_UNSUP
+
+
+def test_attend_decode_gqa_argument_errors(lib):
+    s = Shape(2, 3, 128, 8, 256)      # H = key/value heads
+    f = lib.lookat_attend_decode_gqa
+    ws = lib.lookat_attend_decode_gqa_workspace_bytes
+    L = 1000
+    args = lambda **kw: [kw.get("shape", ctypes.byref(s)), kw.get("group", 4), kw.get("L", L), kw.get("lut", FAKE),
+                         kw.get("codes", FAKE), kw.get("cs", L * 8), kw.get("values", FAKE), kw.get("vs", L * 128),
+                         ctypes.c_float(0.125), kw.get("splits", 1), kw.get("ws", None), kw.get("wsb", 0),
+                         kw.get("out", FAKE), None, None]
+    assert f(*args(group=3)) == E_UNSUP
+    assert f(*args(group=0)) == E_UNSUP
+    assert f(*args(L=0)) == E_SHAPE
+    assert f(*args(lut=None)) == E_NULL
+    assert f(*args(cs=L * 8 - 8)) == E_SHAPE
+    assert f(*args(codes=FAKE + 4)) == E_ALIGN
+    assert f(*args(shape=ctypes.byref(Shape(2, 3, 32, 4, 256)))) == E_UNSUP       # d_k outside {64, 128}
+    need = ws(ctypes.byref(s), 4, L, 3)
+    assert need == 2 * 3 * 4 * 3 * (128 + 2) * 4
+    assert ws(ctypes.byref(s), 4, L, 1) == 0
+    assert f(*args(splits=3)) == E_WS
+    assert f(*args(splits=3, ws=FAKE, wsb=need - 1)) == E_WS

@@ -456,3 +456,44 @@ def test_decode_step_equals_three_calls(lk):
     out1 = lk.lookat_decode_step(q[:, :, 0], keys[:, :, -1], cb, cache, values, scale)
     assert torch.equal(cache, codes3)
     assert float((out1 - out3).abs().max()) <= 1e-5
+
+
+# ---------------------------------------------------------------- grouped queries ----
+
+@pytest.mark.parametrize("d_k,m", [(128, 8), (64, 4), (128, 16), (64, 2), (64, 16)])
+@pytest.mark.parametrize("g", [2, 4, 8])
+@pytest.mark.parametrize("L,splits", [(1, 0), (65, 0), (300, 1), (1000, 3), (2500, 0)])
+def test_attend_decode_gqa_parity(lk, d_k, m, g, L, splits):
+    """g query heads per key/value head: scores and outputs of every query head against the oracle."""
+    B, H = 2, 3
+    rng = np.random.default_rng(9000 + d_k + m + g + L)
+    d_sub = d_k // m
+    cb = (rng.standard_normal((H, m, 256, d_sub)) * 0.7).astype(np.float32)
+    codes = rng.integers(0, 256, size=(B, H, L, m), dtype=np.uint8)
+    v = rng.standard_normal((B, H, L, d_k)).astype(np.float16)
+    q = (rng.standard_normal((B, H * g, 1, d_k)) / 8).astype(np.float16)
+    lut = oracle.build_lut(q, np.repeat(cb, g, axis=0))[:, :, 0]            # [B, H*g, m, 256]
+    scale = 1.0 / math.sqrt(d_k)
+    out_ref, s_ref = oracle.attend_decode_gqa(lut, codes, v, scale, want_scores=True)
+    s_gpu = torch.empty((B, H * g, L), dtype=torch.float32, device="cuda")
+    out = lk.lookat_attend_decode_gqa(dev(lut), dev(codes), dev(v), scale, num_splits=splits, scores_out=s_gpu)
+    assert out.shape == (B, H * g, d_k)
+    codes_q = np.repeat(codes, g, axis=1)                                   # codes as each query head sees them
+    assert_scores_close(s_gpu.cpu().numpy(), s_ref, lut, codes_q)
+    err = np.abs(out.cpu().numpy() - out_ref).max()
+    assert err <= OUT_ATOL, f"max out err {err}"
+
+
+def test_attend_decode_gqa_equals_per_head_calls(lk):
+    """The grouped kernel against lookat_attend_decode on caches repeated per query head, and
+    on views of a longer cache."""
+    B, H, g, L, Lmax, d_k, m = 2, 2, 4, 777, 1024, 128, 8
+    rng = np.random.default_rng(9100)
+    lut = dev((rng.standard_normal((B, H * g, m, 256)) * 2).astype(np.float32))
+    cache_c = torch.randint(0, 256, (B, H, Lmax, m), dtype=torch.uint8, device="cuda")
+    cache_v = torch.randn((B, H, Lmax, d_k), device="cuda").half()
+    codes, values = cache_c[:, :, :L], cache_v[:, :, :L]
+    out = lk.lookat_attend_decode_gqa(lut, codes, values, 0.09)
+    ref = lk.lookat_attend_decode(lut, codes.repeat_interleave(g, dim=1).contiguous(),
+                                  values.repeat_interleave(g, dim=1).contiguous(), 0.09)
+    assert float((out - ref).abs().max()) <= 1e-5

@@ -358,3 +358,72 @@ def test_paper_accounting_matches_array_shapes():
     for m_, name in ((2, "lookat2"), (8, "lookat8"), (16, "lookat16")):
         assert m_ == g[f"{name}_bytes_per_token"]
         assert 2 * 64 // m_ == g[f"{name}_compression"]
+
+
+# ---------------------------------------------------------------- grouped queries ----
+
+def _gqa_case(rng, B=2, H=3, g=4, L=41, d_k=8, m=2):
+    d_sub = d_k // m
+    cb = rng.standard_normal((H, m, 256, d_sub)).astype(np.float32)
+    keys = rng.standard_normal((B, H, L, d_k)).astype(np.float32)
+    v = rng.standard_normal((B, H, L, d_k)).astype(np.float16)
+    q = (rng.standard_normal((B, H * g, 1, d_k)) / 2).astype(np.float32)
+    codes = oracle.encode_keys(keys, cb)
+    # tables of query head hq against the codebooks of key/value head hq // g
+    lut = oracle.build_lut(q, np.repeat(cb, g, axis=0))[:, :, 0]
+    return cb, keys, v, q, codes, lut
+
+
+def test_gqa_equals_numpy_on_shared_heads():
+    """Grouped queries against a numpy evaluation (gather, softmax, weighted sum) that maps query
+    head hq to key/value head hq // g by explicit indexing."""
+    rng = np.random.default_rng(31)
+    for g in (1, 2, 4, 8):
+        cb, keys, v, q, codes, lut = _gqa_case(rng, g=g)
+        out, scores = oracle.attend_decode_gqa(lut, codes, v, 0.3, want_scores=True)
+        B, HQ, m, K = lut.shape
+        L = codes.shape[2]
+        ref_s = np.zeros((B, HQ, L))
+        for hq in range(HQ):
+            for i in range(m):
+                ref_s[:, hq] += np.take_along_axis(lut[:, hq, i].astype(np.float64), codes[:, hq // g, :, i].astype(np.int64), axis=-1)
+        assert np.allclose(scores, ref_s, rtol=0, atol=1e-5)
+        v_exp = np.stack([v[:, hq // g] for hq in range(HQ)], axis=1)
+        ref_o, _ = _np_softmax_attend(ref_s.astype(np.float32), v_exp, 0.3)
+        assert np.allclose(out, ref_o, rtol=0, atol=1e-5)
+
+
+def test_gqa_group_one_is_plain_attention_and_heads_map_by_division():
+    rng = np.random.default_rng(32)
+    cb, keys, v, q, codes, lut = _gqa_case(rng, g=1)
+    assert np.array_equal(oracle.attend_decode_gqa(lut, codes, v, 0.25), oracle.attend_decode(lut, codes, v, 0.25))
+    # changing the values of key/value head 1 changes exactly the outputs of query heads 4..7 (g = 4):
+    # a modulo instead of a division in the head mapping would touch heads 1, 4, 7, 10
+    cb, keys, v, q, codes, lut = _gqa_case(rng, g=4)
+    base = oracle.attend_decode_gqa(lut, codes, v, 0.25)
+    v2 = v.copy()
+    v2[:, 1] += np.float16(1.0)
+    moved = np.abs(oracle.attend_decode_gqa(lut, codes, v2, 0.25) - base).max(axis=(0, 2)) > 0
+    assert moved.tolist() == [False] * 4 + [True] * 4 + [False] * 4
+
+
+def test_gqa_zero_distortion_equals_dense_grouped_attention():
+    """256 keys that are their own centroids: LOOKAT with grouped queries equals dense grouped-query
+    attention softmax(q K^T / sqrt(d_k)) V evaluated by numpy in fp64."""
+    rng = np.random.default_rng(33)
+    B, H, g, L, d_k, m = 1, 2, 4, 256, 16, 4
+    d_sub = d_k // m
+    keys = rng.standard_normal((B, H, L, d_k)).astype(np.float32)
+    cb = np.stack([np.stack([keys[0, h, :, i * d_sub:(i + 1) * d_sub] for i in range(m)]) for h in range(H)])
+    v = rng.standard_normal((B, H, L, d_k)).astype(np.float16)
+    q = (rng.standard_normal((B, H * g, 1, d_k)) / 2).astype(np.float32)
+    codes = oracle.encode_keys(keys, cb)
+    lut = oracle.build_lut(q, np.repeat(cb, g, axis=0))[:, :, 0]
+    out = oracle.attend_decode_gqa(lut, codes, v, 1.0 / math.sqrt(d_k))
+    kx = np.repeat(keys.astype(np.float64), g, axis=1)
+    vx = np.repeat(v.astype(np.float64), g, axis=1)
+    s = np.einsum("bhd,bhld->bhl", q[:, :, 0].astype(np.float64), kx) / math.sqrt(d_k)
+    a = np.exp(s - s.max(-1, keepdims=True))
+    a /= a.sum(-1, keepdims=True)
+    ref = np.einsum("bhl,bhld->bhd", a, vx)
+    assert np.allclose(out, ref, rtol=0, atol=2e-6)

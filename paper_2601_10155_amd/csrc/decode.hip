@@ -586,6 +586,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
+            __builtin_amdgcn_sched_barrier(0);   // request order = need order: codes before value rows
             load_rows<DK, CH>(v, rv, kb, 0, lane);
             consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
         }
@@ -611,7 +612,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     }
     __syncthreads();
 
-    for (int x = tid; x < G * DK; x += NT) {   // (query head of the group, output coordinate)
+    auto finish = [&](int x) {   // x = (query head of the group, output coordinate)
         const int g = x / DK, j = x % DK;
         float mx = -INFINITY;
 #pragma unroll
@@ -635,6 +636,13 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
                 dst[DK + 1] = zz;
             }
         }
+    };
+    if constexpr (G * DK <= NT) {
+        if (tid < G * DK)
+            finish(tid);
+    } else {
+        for (int x = tid; x < G * DK; x += NT)
+            finish(x);
     }
 }
 

@@ -479,7 +479,7 @@ def test_attend_decode_gqa_parity(lk, d_k, m, g, L, splits):
     out = lk.lookat_attend_decode_gqa(dev(lut), dev(codes), dev(v), scale, num_splits=splits, scores_out=s_gpu)
     assert out.shape == (B, H * g, d_k)
     codes_q = np.repeat(codes, g, axis=1)                                   # codes as each query head sees them
-    assert_scores_close(s_gpu.cpu().numpy(), s_ref, lut, codes_q)
+    assert_scores_close(s_gpu.cpu().numpy(), lut, codes_q, s_ref)
     err = np.abs(out.cpu().numpy() - out_ref).max()
     assert err <= OUT_ATOL, f"max out err {err}"
 

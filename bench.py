@@ -65,6 +65,9 @@ def parse_args():
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
                     help="fused: one lookat_decode_step per layer; calls: encode_keys + build_lut + attend_decode; "
                          "auto: fused when the library would use a single range per (b,h)")
+    ap.add_argument("--group", type=int, default=1, choices=[1, 2, 4, 8],
+                    help="decode workloads: query heads per key/value head (grouped-query attention): the workload's H "
+                         "query heads share H/group key/value heads; times lookat_attend_decode_gqa")
     ap.add_argument("--kmeans-iters", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
@@ -111,6 +114,9 @@ def main():
     cfg = li.CONFIGS[args.workload]
     if cfg.T > 1:
         prefill_main(args, cfg, lk, li, torch, device)
+        return
+    if args.group > 1:
+        gqa_main(args, cfg, lk, li, torch, device)
         return
     scale = 1.0 / math.sqrt(cfg.d_k)
     layers = [Layer(lk, li, cfg, device, i, args.kmeans_iters) for i in range(cfg.layers)]
@@ -257,6 +263,99 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, layers, scale, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def gqa_main(args, cfg, lk, li, torch, device):
+    """Decode step with grouped queries: the workload's H query heads share H/group key/value heads.
+    Per layer: encode the new key of every key/value head, build the tables of every query head
+    (against its key/value head's codebooks), lookat_attend_decode_gqa.  One JSON line; the roofline
+    is the grouped decode kernel against the key/value bytes it streams (once for the whole group)."""
+    g = args.group
+    if cfg.H % g:
+        raise SystemExit(f"--group {g} does not divide the workload's {cfg.H} heads")
+    kv = li.shrink(cfg, H=cfg.H // g)
+    scale = 1.0 / math.sqrt(cfg.d_k)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(li.BASE_SEED + 977)
+    layers = []
+    for i in range(cfg.layers):
+        ly = Layer(lk, li, kv, device, i, args.kmeans_iters)
+        ly.cb_q = ly.cb.repeat_interleave(g, dim=0).contiguous()     # codebooks as each query head sees them
+        ly.q = (torch.randn((cfg.B, cfg.H, 1, cfg.d_k), generator=gen, device=device) / 8).to(ly.q.dtype)
+        ly.lut = torch.empty((cfg.B, cfg.H, 1, cfg.m, cfg.K), dtype=torch.float32, device=device)
+        ly.out = torch.empty((cfg.B, cfg.H, cfg.d_k), dtype=torch.float32, device=device)
+        layers.append(ly)
+    splits = lk.attend_decode_auto_splits(kv.B, kv.H, kv.d_k, kv.m, kv.L)
+    ws = torch.empty(max(16, cfg.B * cfg.H * splits * (cfg.d_k + 2) * 4), dtype=torch.uint8, device=device)
+
+    def decode_only(ly):
+        lk.lookat_attend_decode_gqa(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
+                                    num_splits=splits, workspace=ws, out=ly.out)
+
+    def step():
+        for ly in layers:
+            lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
+            lk.lookat_build_lut(ly.q, ly.cb_q, lut_out=ly.lut)
+            decode_only(ly)
+
+    step()
+    torch.cuda.synchronize()
+    # the grouped kernel against the plain kernel on caches repeated per query head (layer 0)
+    ly = layers[0]
+    ref = lk.lookat_attend_decode(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K),
+                                  ly.codes.repeat_interleave(g, dim=1).contiguous(),
+                                  ly.values.repeat_interleave(g, dim=1).contiguous(), scale)
+    max_diff = float((ref - ly.out).abs().max())
+    del ref
+    run_step = step
+    if args.mode == "graph":
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_launch = max(args.steps, 20) * cfg.layers
+    for ly in layers:
+        decode_only(ly)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n_launch):
+        decode_only(layers[i % cfg.layers])
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / n_launch
+    kv_bytes = kv.B * kv.H * kv.L * (kv.m + 2 * kv.d_k)
+    scores_per_step = cfg.layers * cfg.B * cfg.H * cfg.L
+    print(json.dumps({
+        "metric": "LUT-attention decode with grouped queries: (query head, key) scores/sec/GPU; achieved HBM GB/s vs peak",
+        "value": scores_per_step * args.steps / elapsed, "unit": "keys/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} with grouped queries: B={cfg.B} query heads={cfg.H} key/value heads={kv.H} "
+                               f"(group={g}) L={cfg.L} d_k={cfg.d_k} m={cfg.m} layers={cfg.layers}; per layer "
+                               "encode(1 new key) + build_lut + attend_decode_gqa",
+                   "launch": args.mode, "num_splits": splits},
+        "roofline": {"bound": "hbm", "kernel": f"lookat::decode_split_kernel (group of {g} query heads)",
+                     "achieved": kv_bytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": kv_bytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": kv_bytes,
+                     "us_per_launch": us, "launches_timed": n_launch,
+                     "query_head_bytes_equivalent_GBs": kv_bytes * g / us / 1e3,
+                     "max_abs_diff_vs_ungrouped_kernel": max_diff},
+    }), flush=True)
 
 
 def prefill_main(args, cfg, lk, li, torch, device):

@@ -440,7 +440,9 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
 // G > 1: grouped-query attention: the workgroup's (b,h) is a KEY/VALUE head shared by G query heads,
 // whose tables (contiguous in memory) are all staged in LDS; codes and values are streamed once.
-template <int DK, int M, int WAVES, int OCC, typename FT = void, int G = 1>
+// PF: tiles of a wavefront requested before anything else is done (1, or more for the fused step,
+// whose table build and key encoding would otherwise leave the memory pipe idle for microseconds).
+template <int DK, int M, int WAVES, int OCC, typename FT = void, int G = 1, int PF = 1>
 __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_DECODE_HEAD_PARAMS,
                                                                          const DecodeLate late)
 {
@@ -516,12 +518,21 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     const int rowin = lane / LPR;    // which row of a wave-wide load
     const uint32_t kofs = (uint32_t)(RPL * sub + rowin);
     uint32_t kb = k0 + (uint32_t)wave * kTile;
-    KeyCodes<M ? M : 4> kc;
-    if constexpr (M != 0)
-        kc.load(rc, (kb + kofs) * M);
-    __builtin_amdgcn_sched_barrier(0);   // keep the request order: codes before value rows
-    v4u v[CH];
-    load_rows<DK, CH>(v, rv, kb, 0, lane);
+    KeyCodes<M ? M : 4> kcs[PF];
+    v4u vs[PF][CH];
+#pragma unroll
+    for (int t = 0; t < PF; ++t) {
+        // Unconditional: requests past the range return zero (descriptor bounds).  Behind a branch
+        // the compiler could no longer count how many requests follow a given one, and every wait
+        // would become a wait for all of them.
+        const uint32_t kbt = kb + (uint32_t)t * NT;
+        if constexpr (M != 0)
+            kcs[t].load(rc, (kbt + kofs) * M);
+        __builtin_amdgcn_sched_barrier(0);   // keep the request order: codes before value rows
+        load_rows<DK, CH>(vs[t], rv, kbt, 0, lane);
+    }
+    KeyCodes<M ? M : 4> &kc = kcs[0];
+    v4u(&v)[CH] = vs[0];
     if constexpr (FUSED) {
         // While the first tile is in flight: thread c takes centroid c of each subspace from the
         // (L2-resident) codebook of the head, and from the same row computes
@@ -583,6 +594,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     SoftmaxState<G> st;
     if (kb < k1) {
         consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+#pragma unroll
+        for (int t = 1; t < PF; ++t) {   // the other tiles requested at the start
+            kb += NT;
+            if (kb < k1)
+                consume_tile<DK, M, CH, FUSED, G>(a, st, kcs[t], vs[t], lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+        }
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
@@ -817,7 +834,12 @@ static int pick_waves(int d_k, int m, int64_t keys_per_split)
     return keys_per_split >= 32 * kTile ? 16 : 4;
 }
 
-// Fused decode step: one workgroup of 256 threads per (b,h), one range.
+// Fused decode step: one workgroup of 256 threads per (b,h), one range.  Every wavefront requests
+// its first kStepPrefetch tiles before the table build.  Measured at B=32, H=12, L=1024, m=4
+// (us per launch): 1 tile 14.0, 2 tiles 13.8, 4 tiles (at two wavefronts per SIMD) 15.9: with
+// everything requested at once the codebook rows (L2 hits) queue behind a compute unit's worth of
+// HBM misses.  m = 16 keeps one tile (registers).
+constexpr int kStepPrefetch = 2;
 template <int DK, typename FT>
 static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
@@ -826,19 +848,19 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
                        (size_t)a.m * kDecWaves * (sizeof(double) + sizeof(int));
     switch (a.m) {
     case 2:   // 32- or 64-coordinate rows: give the register allocator the larger budget
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 4:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 8:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 16:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT, 1, 1>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     default:

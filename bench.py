@@ -400,6 +400,15 @@ def prefill_main(args, cfg, lk, li, torch, device):
         torch.cuda.synchronize()
         us[name] = e0.elapsed_time(e1) * 1e3 / args.steps
 
+    # plain write stream over the table buffer: what the HBM write path delivers
+    lk.lookat_probe_stream_write(lut, 0)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        lk.lookat_probe_stream_write(lut, 0)
+    e1.record()
+    torch.cuda.synchronize()
+    write_stream_gbs = lut.numel() * 4 / (e0.elapsed_time(e1) * 1e3 / args.steps) / 1e3
     BH, nk = cfg.B * cfg.H, cfg.B * cfg.H * cfg.L
     pairs = BH * (cfg.T * (cfg.T + 1) // 2 + cfg.T * (cfg.L - cfg.T))        # visible (query, key) pairs
     enc_ops = nk * cfg.d_k * cfg.K * 3                                          # sub, mul, add in fp64 per (key, centroid, coordinate)
@@ -424,7 +433,8 @@ def prefill_main(args, cfg, lk, li, torch, device):
                      "achieved": lds_bytes / us["score_prefill"] / 1e3, "peak": LDS_PEAK, "unit": "GB/s",
                      "frac": lds_bytes / us["score_prefill"] / 1e3 / LDS_PEAK,
                      "traffic": counted_traffic((cfg.name, "score_prefill")),
-                     "us_per_launch": us["score_prefill"], "scores_written_GBs": score_bytes / us["score_prefill"] / 1e3},
+                     "us_per_launch": us["score_prefill"], "scores_written_GBs": score_bytes / us["score_prefill"] / 1e3,
+                     "write_stream_GBs": write_stream_gbs},
         "kernels": {
             "encode_filter_kernel": {"bound": "alu", "us": us["encode_keys"],
                                      "achieved": cand * 4 / us["encode_keys"] / 1e6, "peak": VALU_PEAK,

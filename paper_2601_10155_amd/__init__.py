@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     lookat_kmeans,
     lookat_kmeans_step,
     lookat_probe_stream_read,
+    lookat_probe_stream_write,
     lookat_score_prefill,
     version,
 )
@@ -31,5 +32,5 @@ __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
     "lookat_attend_decode", "lookat_attend_decode_gqa", "lookat_build_lut", "lookat_decode_step", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
-    "lookat_probe_stream_read", "lookat_score_prefill",
+    "lookat_probe_stream_read", "lookat_probe_stream_write", "lookat_score_prefill",
 ]

@@ -66,6 +66,8 @@ def load_library():
         lib.lookat_kmeans_step.restype = ctypes.c_int
         lib.lookat_probe_stream_read.argtypes = [vp, sz, vp, vp]
         lib.lookat_probe_stream_read.restype = ctypes.c_int
+        lib.lookat_probe_stream_write.argtypes = [vp, sz, ctypes.c_uint32, vp]
+        lib.lookat_probe_stream_write.restype = ctypes.c_int
         lib.lookat_last_error.restype = ctypes.c_char_p
         lib.lookat_version.restype = ctypes.c_int
         _lib = lib
@@ -355,6 +357,16 @@ def lookat_probe_stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
         raise ValueError("src must be contiguous")
     _check(lib.lookat_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
                                         _stream(src)))
+
+
+def lookat_probe_stream_write(dst: torch.Tensor, word: int = 0) -> None:
+    """Measurement aid: overwrites all bytes of `dst` once with a 32-bit pattern through a plain write kernel."""
+    lib = load_library()
+    _dev(dst, "dst")
+    if not dst.is_contiguous():
+        raise ValueError("dst must be contiguous")
+    _check(lib.lookat_probe_stream_write(dst.data_ptr(), dst.numel() * dst.element_size(), int(word) & 0xffffffff,
+                                         _stream(dst)))
 
 
 # short aliases

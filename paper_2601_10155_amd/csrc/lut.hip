@@ -94,8 +94,8 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_generic_kernel(const QT
 // One wavefront owns 32-query tiles and keeps the whole [d_sub x 256] codebook slice in
 // registers as MFMA B-fragments; per tile it issues 8 column blocks x d_sub/2 steps of
 // v_mfma_f32_32x32x2_f32 (fp32 in, fp32 accumulate: same accuracy class as the vector kernel)
-// and streams the 32 x 256 fp32 results out, each store instruction writing two full 128-byte
-// rows segments.  The kernel is bound by that output stream (d_sub*2 flops per 4 bytes
+// and streams the 32 x 256 fp32 results out through an LDS transpose, 16 bytes per lane and 512
+// contiguous bytes per half-wavefront.  The kernel is bound by that output stream (d_sub*2 flops per 4 bytes
 // written), not by the matrix cores.
 //   fragment layout of the 32x32x2 MFMA: A[row = lane%32][k = lane/32], B[k = lane/32][col = lane%32],
 //   D[row = 8*(r/4) + 4*(lane/32) + r%4][col = lane%32] for accumulator register r = 0..15.
@@ -117,6 +117,9 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void build_lut_mfma_kernel(const
     const int kh = lane >> 5;
     const int64_t nq = (int64_t)B * T;
     const int64_t ntiles = (nq + 31) / 32;
+    constexpr int kStageStride = 128;       // floats per staged query row: 4 wavefronts x 16 KB = the 64 KB of static LDS
+    __shared__ __align__(16) float stage_s[kMfmaWaves][32 * kStageStride];
+    float *stage = stage_s[wave];
 
     float bfrag[8][KS];
     {
@@ -140,31 +143,47 @@ __global__ __launch_bounds__(kMfmaWaves *kWave) void build_lut_mfma_kernel(const
             for (int s = 0; s < KS; ++s)
                 afrag[s] = live ? to_f32<QT>(src[2 * s]) : 0.f;
         }
-        // output row offsets of the 16 accumulator registers of this lane
-        int64_t row_off[16];
+        // The accumulator layout gives a lane one column (centroid) and 16 rows (queries): stored
+        // directly, every store instruction would write 4 bytes per lane (two 128-byte pieces per
+        // wavefront), and the kernel is then limited by store-instruction issue, not by HBM.  So the
+        // results cross LDS: four column blocks (128 centroids) of the 32 queries are written as
+        // [query][128] and read back 16 bytes per lane, 512 contiguous bytes of a table row per
+        // half-wavefront, and stored with 16-byte stores.
+        const int64_t r0 = tile * 32;
+        const int64_t b0 = r0 / T;
+        const int t0 = (int)(r0 % T);
 #pragma unroll
-        for (int rr = 0; rr < 16; ++rr) {
-            const int64_t r = tile * 32 + 8 * (rr / 4) + 4 * kh + (rr % 4);
-            if (r < nq) {
-                const int64_t b = r / T, t = r % T;
-                row_off[rr] = ((((b * H + h) * T + t) * m) + i) * kCentroids + n;
-            } else {
-                row_off[rr] = -1;
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const int nt = 4 * half + nb;
+                v16f acc;
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr)
+                    acc[rr] = 0.f;
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag[s], bfrag[nt][s], acc, 0, 0, 0);
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr)
+                    stage[(8 * (rr / 4) + 4 * kh + (rr % 4)) * kStageStride + nb * 32 + n] = acc[rr];
             }
-        }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
-            v16f acc;
-#pragma unroll
-            for (int rr = 0; rr < 16; ++rr)
-                acc[rr] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag[s], bfrag[nt][s], acc, 0, 0, 0);
-#pragma unroll
-            for (int rr = 0; rr < 16; ++rr)
-                if (row_off[rr] >= 0)
-                    lut[row_off[rr] + nt * 32] = acc[rr];
+            for (int rp = 0; rp < 16; ++rp) {
+                const int row = 2 * rp + kh;                  // lanes 0..31: one query, lanes 32..63: the next
+                const float4 v = *reinterpret_cast<const float4 *>(stage + row * kStageStride + 4 * n);
+                const int rr = t0 + row;                      // position of the query within its batch entry, unwrapped
+                const int64_t bq = b0 + rr / T;
+                const int tq = rr % T;
+                if (r0 + row < nq) {
+                    float *dst = lut + ((((bq * H + h) * T + tq) * m) + i) * kCentroids + half * 128 + 4 * n;
+                    *reinterpret_cast<float4 *>(dst) = v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_wave_barrier();              // the next half overwrites the staging area
         }
     }
 }

@@ -1,5 +1,5 @@
-// Plain read-stream kernel used to measure what the HBM read path delivers on the buffers
-// the decode kernel streams (a ceiling for its bandwidth figure, not part of the method).
+// Plain read-stream and write-stream kernels used to measure what the HBM paths deliver on the
+// buffers the kernels stream (ceilings for their bandwidth figures, not part of the method).
 #include "common.h"
 #include "lookat_probe.h"
 
@@ -26,7 +26,39 @@ __global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const uint4 
         sink[0] = x;
 }
 
+__global__ __launch_bounds__(kProbeThreads) void stream_write_kernel(uint4 *__restrict__ p, size_t n16, uint32_t word)
+{
+    const size_t base = (size_t)blockIdx.x * (kProbeLoads * kProbeThreads) + threadIdx.x;
+    const uint4 v = make_uint4(word, word, word, word);
+#pragma unroll
+    for (int j = 0; j < kProbeLoads; ++j) {
+        const size_t i = base + (size_t)j * kProbeThreads;
+        if (i < n16)
+            p[i] = v;
+    }
+}
+
 }  // namespace lookat
+
+extern "C" int lookat_probe_stream_write(void *dst, size_t bytes, uint32_t word, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (!dst)
+        return fail(LOOKAT_ERR_NULL, "dst must be non-NULL");
+    if (bytes == 0 || (bytes % 16))
+        return fail(LOOKAT_ERR_SHAPE, "bytes=%zu must be a positive multiple of 16", bytes);
+    if (!aligned16(dst))
+        return fail(LOOKAT_ERR_ALIGN, "dst must be 16-byte aligned");
+    const size_t n16 = bytes / 16;
+    const size_t per_block = (size_t)kProbeLoads * kProbeThreads;
+    const size_t blocks = (n16 + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffULL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "bytes=%zu exceed one launch", bytes);
+    hipLaunchKernelGGL(stream_write_kernel, dim3((unsigned)blocks), dim3(kProbeThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint4 *>(dst), n16, word);
+    return check_launch("lookat_probe_stream_write");
+}
 
 extern "C" int lookat_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
 {

@@ -121,6 +121,10 @@ def test_kmeans_and_probe_argument_errors(lib):
     assert p(None, 1024, FAKE, None) == E_NULL
     assert p(FAKE, 1000, FAKE, None) == E_SHAPE
     assert p(FAKE + 8, 1024, FAKE, None) == E_ALIGN
+    w = lib.lookat_probe_stream_write
+    assert w(None, 1024, 0, None) == E_NULL
+    assert w(FAKE, 1000, 0, None) == E_SHAPE
+    assert w(FAKE + 8, 1024, 0, None) == E_ALIGN
 
 
 def test_score_prefill_argument_errors(lib):

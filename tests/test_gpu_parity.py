@@ -497,3 +497,11 @@ def test_attend_decode_gqa_equals_per_head_calls(lk):
     ref = lk.lookat_attend_decode(lut, codes.repeat_interleave(g, dim=1).contiguous(),
                                   values.repeat_interleave(g, dim=1).contiguous(), 0.09)
     assert float((out - ref).abs().max()) <= 1e-5
+
+
+def test_probe_stream_write_fills_exactly_the_buffer(lk):
+    buf = torch.zeros(4096 + 8, dtype=torch.int32, device="cuda")
+    lk.lookat_probe_stream_write(buf[4:4 + 4096], 0x5A5A1234)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert (host[4:4 + 4096] == 0x5A5A1234).all() and (host[:4] == 0).all() and (host[-4:] == 0).all()

@@ -20,6 +20,8 @@
 //     four queries' entries for centroid c: exactly one 16-byte LDS store.  On the vector ALU the
 //     same build costs 4 FMAs and an LDS operand read per (centroid, coordinate) and was 60% of
 //     the kernel's LDS instructions;
+//   * a thread scores four consecutive keys per step, so its 4 x 4 results leave as one 16-byte
+//     store per query row (1 KB contiguous per wavefront and instruction);
 //   * the scoring loop is bound by LDS gather bandwidth (4 bytes per (query, key, subspace)) and by
 //     the scores written to HBM (4 bytes per (query, key), masked ones included).  The gathers hit
 //     random bank groups: an LDS read of 16 bytes per lane is served 8 lanes at a time and 8 random
@@ -60,6 +62,7 @@ struct PrefillArgs {
     int tiles;                // ceil(T / 4)
     int BH;
     int groups;               // ceil(tiles / kPfGroup)
+    int vec4;                 // L % 4 == 0 and scores 16-byte aligned: rows take 16-byte stores
 };
 
 template <int M>
@@ -91,7 +94,7 @@ struct PfCodes {
 template <int M>
 __device__ __forceinline__ pf_v4f pf_score_key(const float *lut_s, const PfCodes<M> &kc)
 {
-    constexpr int GB = M < 4 ? M : 4;
+    constexpr int GB = M < 8 ? M : 8;
     pf_v4f s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i0 = 0; i0 < M; i0 += GB) {
@@ -188,12 +191,19 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
         // build: by then the previous tile's score stores, which that wait also covers, have drained.
         if (tile > tile_lo)
             fetch_q(tile - 1);
-        // codes of this thread's first two keys: requested now, needed after the build
-        PfCodes<M> kc0, kc1;
-        if (tid < kmax)
-            kc0.load(codes_bh + (int64_t)tid * M);
-        if (tid + NT < kmax)
-            kc1.load(codes_bh + (int64_t)(tid + NT) * M);
+        // codes of this thread's first four keys (4*tid .. 4*tid+3): requested now, needed after the build
+        // (always issued, at an index clamped into the cache: plain values, no partly written arrays)
+        const int last_key = (int)(a.L - 1);
+        PfCodes<M> kc0, kc1, kc2, kc3;
+#define LOOKAT_PF_LOAD_QUAD(l0_)                                                             \
+    do {                                                                                     \
+        const int q0_ = (l0_);                                                               \
+        kc0.load(codes_bh + (int64_t)(q0_ < last_key ? q0_ : last_key) * M);                 \
+        kc1.load(codes_bh + (int64_t)(q0_ + 1 < last_key ? q0_ + 1 : last_key) * M);         \
+        kc2.load(codes_bh + (int64_t)(q0_ + 2 < last_key ? q0_ + 2 : last_key) * M);         \
+        kc3.load(codes_bh + (int64_t)(q0_ + 3 < last_key ? q0_ + 3 : last_key) * M);         \
+    } while (0)
+        LOOKAT_PF_LOAD_QUAD(4 * tid);
 
         // ---- tables as [i][c][4]: lut4[i*256 + c] = (q[t]^(i) . C_i[c])_{t=0..3}, j ascending ----
         // Two subspaces at a time: their accumulator chains are independent, so one chain's
@@ -220,46 +230,61 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
         cur ^= 1;
         __syncthreads();
 
-        // ---- scoring: two keys per thread and step, four scores per key ----
-        // score rows of the tile: uniform bases (scalar registers) indexed by the 32-bit key number
-        float *rowp[TQ];
+        // ---- scoring: four consecutive keys per thread and step, four scores per key ----
+        // A thread's 4 keys x 4 queries come out as four 16-byte pieces, one per query row, so a
+        // wavefront writes 1 KB of contiguous scores per store instruction (with one key per lane
+        // it would be 256 bytes, and the kernel's 2 GB of output four times the store instructions).
+        float *rowp[TQ];   // score rows of the tile: uniform bases (scalar registers)
 #pragma unroll
         for (int t = 0; t < TQ; ++t)
             rowp[t] = scores_bh + (int64_t)(t0 + t) * a.L;
-        auto put = [&](int l, const pf_v4f &sc) {
+        for (int l0 = 4 * tid; l0 < kmax; l0 += 4 * NT) {
+            pf_v4f sc[4];
+            sc[0] = pf_score_key<M>(lut_s, kc0);
+            sc[1] = pf_score_key<M>(lut_s, kc1);
+            __builtin_amdgcn_sched_barrier(0);   // two keys' gathers in flight at a time: more would only fill registers
+            sc[2] = pf_score_key<M>(lut_s, kc2);
+            sc[3] = pf_score_key<M>(lut_s, kc3);
+            __builtin_amdgcn_sched_barrier(0);
+            LOOKAT_PF_LOAD_QUAD(l0 + 4 * NT);    // next keys of this thread (clamped: harmless past the end)
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 const int tq = t0 + t;
-                if (tq < a.T)
-                    rowp[t][(uint32_t)l] = (l <= tq + off) ? sc[t] : -INFINITY;
+                if (tq >= a.T)
+                    continue;
+                pf_v4f o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    o[j] = (l0 + j <= tq + off) ? sc[j][t] : -INFINITY;   // keys of the quad past the tile's range are masked too
+                if (a.vec4) {
+                    *reinterpret_cast<pf_v4f *>(rowp[t] + (uint32_t)l0) = o;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (l0 + j < a.L)
+                            rowp[t][(uint32_t)(l0 + j)] = o[j];
+                }
             }
-        };
-        for (int l = tid; l < kmax; l += 2 * NT) {
-            const int l1 = l + NT;
-            const bool has1 = l1 < kmax;
-            const pf_v4f s0 = pf_score_key<M>(lut_s, kc0);
-            pf_v4f s1 = {0.f, 0.f, 0.f, 0.f};
-            if (has1)
-                s1 = pf_score_key<M>(lut_s, kc1);
-            const int n0 = l + 2 * NT, n1 = l1 + 2 * NT;
-            if (n0 < kmax)
-                kc0.load(codes_bh + (int64_t)n0 * M);   // next keys of this thread
-            if (n1 < kmax)
-                kc1.load(codes_bh + (int64_t)n1 * M);
-            put(l, s0);
-            if (has1)
-                put(l1, s1);
         }
-        // ---- keys no query of the tile may see ----
+        // ---- keys no query of the tile may see (from the end of the last quad on) ----
+        const int64_t kfill = ((int64_t)kmax + 3) / 4 * 4;
         for (int t = 0; t < TQ; ++t) {
             const int tq = t0 + t;
             if (tq >= a.T)
                 break;
-            for (int64_t l = kmax + tid; l < a.L; l += NT)
-                scores_bh[(int64_t)tq * a.L + l] = -INFINITY;
+            if (a.vec4) {
+                const pf_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                for (int64_t l = kfill + 4 * tid; l < a.L; l += 4 * NT)
+                    *reinterpret_cast<pf_v4f *>(rowp[t] + l) = ninf;
+            } else {
+                for (int64_t l = kfill + tid; l < a.L; l += NT)
+                    rowp[t][l] = -INFINITY;
+            }
         }
     }
 }
+
+#undef LOOKAT_PF_LOAD_QUAD
 
 template <typename QT, int DK, int M>
 static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
@@ -347,6 +372,7 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
     a.tiles = 0;
     a.BH = 0;
     a.groups = 0;
+    a.vec4 = (L % 4 == 0) && aligned16(scores);
     hipStream_t st = static_cast<hipStream_t>(stream);
     return (q_dtype == LOOKAT_F16) ? dispatch_prefill<__half>(shape, a, st) : dispatch_prefill<float>(shape, a, st);
 }

@@ -68,6 +68,10 @@ def parse_args():
     ap.add_argument("--group", type=int, default=1, choices=[1, 2, 4, 8],
                     help="decode workloads: query heads per key/value head (grouped-query attention): the workload's H "
                          "query heads share H/group key/value heads; times lookat_attend_decode_gqa")
+    ap.add_argument("--codes", default="encoded", choices=["encoded", "uniform"],
+                    help="encoded: the cache holds the codes lookat_encode_keys gives the seeded keys (skewed, correlated "
+                         "histograms, as real caches have); uniform: independent uniform random bytes, the worst case for "
+                         "LDS bank conflicts of the table gathers")
     ap.add_argument("--kmeans-iters", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
@@ -120,6 +124,11 @@ def main():
         return
     scale = 1.0 / math.sqrt(cfg.d_k)
     layers = [Layer(lk, li, cfg, device, i, args.kmeans_iters) for i in range(cfg.layers)]
+    if args.codes == "uniform":
+        gen = torch.Generator(device=device)
+        gen.manual_seed(li.BASE_SEED + 4242)
+        for ly in layers:
+            ly.codes.copy_(torch.randint(0, 256, ly.codes.shape, generator=gen, device=device, dtype=torch.uint8))
     splits = lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L)
     ws_bytes = lk.attend_decode_workspace_bytes(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, splits)
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=device)
@@ -238,7 +247,7 @@ def main():
                         f"layers={cfg.layers}; per layer encode(1 new key) + build_lut + attend_decode",
             "path": "lookat_decode_step (one fused kernel per layer)" if fused
                     else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode",
-            "values": "fp16", "codes": "u8", "lut": "f32", "launch": args.mode, "num_splits": splits,
+            "values": "fp16", "codes": "u8 (" + args.codes + ")", "lut": "f32", "launch": args.mode, "num_splits": splits,
             "codebooks": f"{args.kmeans_iters} Lloyd iterations (lookat_kmeans_step) on {cfg.n_calib} seeded "
                          "calibration keys per head",
         },
@@ -450,7 +459,36 @@ def prefill_main(args, cfg, lk, li, torch, device):
                                       "mfma_TFLOPs": lut_flops / us["build_lut"] / 1e6, "mfma_peak_fp32_TFLOPs": 157.3},
         },
     }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = prefill_cpu_baseline(cfg, keys, q, cb, codes, scores, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def prefill_cpu_baseline(cfg, keys, q, cb, codes, scores, budget_s):
+    """The CPU oracle on one batch entry of the block, a few heads: encode, tables, causal scoring;
+    checks the GPU's codes and scores of those heads against it."""
+    import numpy as np
+
+    import oracle
+
+    nh = 2
+    k = keys[0:1, :nh].cpu().numpy()
+    qq = q[0:1, :nh].cpu().numpy()
+    cbn = cb[:nh].cpu().numpy()
+    t0 = time.perf_counter()
+    c_ref = oracle.encode_keys(k, cbn)
+    lut = oracle.build_lut(qq, cbn)
+    s_ref = oracle.score_prefill(lut, c_ref)
+    dt = time.perf_counter() - t0
+    pairs = nh * (cfg.T * (cfg.T + 1) // 2 + cfg.T * (cfg.L - cfg.T))
+    codes_ok = bool(np.array_equal(codes[0:1, :nh].cpu().numpy(), c_ref))
+    got = scores[0:1, :nh].cpu().numpy()
+    vis = np.isfinite(s_ref)
+    err = float(np.max(np.abs(np.where(vis, got, 0.0) - np.where(vis, s_ref, 0.0))))
+    return {"value": pairs / dt, "unit": "pairs/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"batch entry 0, heads 0..{nh - 1} of {cfg.H}: encode {cfg.L} keys, tables of {cfg.T} queries, "
+                      "causal scoring; fp64, one pass",
+            "codes_bit_exact_vs_oracle": codes_ok, "max_abs_score_diff_gpu_vs_oracle": err}
 
 
 def cpu_baseline(cfg, layers, scale, budget_s):

@@ -868,7 +868,8 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
     }
 }
 
-// Grouped queries: 256-thread workgroups, two wavefronts per SIMD (G accumulator sets per lane).
+// Grouped queries: 256-thread workgroups; four wavefronts per SIMD up to G = 4 (G accumulator sets
+// per lane fit 128 registers), two for G = 8.
 template <int DK, int G>
 static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
@@ -876,7 +877,7 @@ static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
     const size_t lds = ((size_t)G * a.m * kCentroids + (size_t)kDecWaves * G * (DK + 2)) * sizeof(float);
 #define LOOKAT_GQA_CASE(M_)                                                                                    \
     case M_: {                                                                                                 \
-        auto kern = decode_split_kernel<DK, M_, kDecWaves, 2, void, G>;                                        \
+        auto kern = decode_split_kernel<DK, M_, kDecWaves, (G <= 4 ? 4 : 3), void, G>;                         \
         if (lds > 64 * 1024) {                                                                                 \
             static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
             if (!configured) {                                                                                 \

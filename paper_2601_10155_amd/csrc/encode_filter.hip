@@ -433,8 +433,7 @@ static bool launch_encode_filter_t(const lookat_shape *s, int64_t N, const void 
     const int64_t total_blocks = (int64_t)s->B * blocks_per_bh;
     // enough workgroups to fill the chip several times over, and at least 8 key blocks per wavefront
     // so that loading the codebook (the price of a wavefront) is amortised
-    static const int64_t target_wgs = getenv("LOOKAT_EF_WGS") ? atoi(getenv("LOOKAT_EF_WGS")) : 2048;
-    int64_t splits = (target_wgs + (int64_t)s->H * s->m - 1) / ((int64_t)s->H * s->m);
+    int64_t splits = (2048 + (int64_t)s->H * s->m - 1) / ((int64_t)s->H * s->m);
     const int64_t by_work = (total_blocks + kEfWaves * 8 - 1) / (kEfWaves * 8);
     if (splits > by_work)
         splits = by_work;

@@ -67,7 +67,10 @@ typedef struct {
  * The squared distance is evaluated in fp64, coordinates in ascending order,
  * with a separately rounded subtract, multiply and add per coordinate (no fused
  * multiply-add); among equal distances the lowest index c wins.  The result is
- * therefore unique and reproducible bit for bit.
+ * therefore unique and reproducible bit for bit.  (The kernels may rank the centroids
+ * with a cheaper product first and evaluate this rule only where the ranking cannot
+ * decide; the codes are those of the rule in every case.  Setting the environment
+ * variable LOOKAT_ENCODE_EXACT=1 makes every call evaluate the rule for all centroids.)
  *
  *   keys       [B,H,N,d_k]  key_dtype (fp16 or fp32), 16-byte aligned, dense
  *   codebooks  [H,m,K,d_sub] fp32, 16-byte aligned (one set per head)

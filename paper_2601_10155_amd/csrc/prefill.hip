@@ -37,7 +37,9 @@ namespace lookat {
 
 constexpr int kPfThreads = 256;   // = centroids per subspace: thread c owns centroid c
 constexpr int kPfTQ = 4;      // queries per tile
-constexpr int kPfGroup = 8;   // query tiles per workgroup (codebook registers reused)
+constexpr int kPfGroup = 8;   // query tiles per workgroup (codebook registers reused) for 2-byte queries ...
+template <typename QT>
+constexpr int pf_group() { return sizeof(QT) == 2 ? kPfGroup : kPfGroup / 2; }   // ... half as many for fp32: the group's queries wait in LDS
 
 typedef unsigned int pf_v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int pf_v2u __attribute__((ext_vector_type(2)));
@@ -61,7 +63,7 @@ struct PrefillArgs {
     int H;
     int tiles;                // ceil(T / 4)
     int BH;
-    int groups;               // ceil(tiles / kPfGroup)
+    int groups;               // ceil(tiles / tiles per workgroup)
     int vec4;                 // L % 4 == 0 and scores 16-byte aligned: rows take 16-byte stores
 };
 
@@ -118,11 +120,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
     constexpr int DSUB = DK / M;
     constexpr int QE = TQ * DK / NT;               // query elements staged per thread and tile
     constexpr int QS = DK + 4;                     // row stride of q_s in floats
+    constexpr int GROUP = pf_group<QT>();
     static_assert(NT == kCentroids, "thread c owns centroid c");
     static_assert(DSUB % 4 == 0 && M % 2 == 0 && (TQ * DK) % NT == 0, "operand reads are 16 bytes wide");
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                           // [M][256][TQ]
     float *q_s = smem + M * kCentroids * TQ;       // [2][TQ][QS]: rows 16 bytes apart modulo the 128-byte bank row
+    QT *q_all = reinterpret_cast<QT *>(q_s + 2 * TQ * QS);   // [GROUP][TQ][DK]: the queries of all the workgroup's tiles, as given
     pf_v4f *lut4 = reinterpret_cast<pf_v4f *>(lut_s);
 
     // Workgroup ids are dealt round-robin to the 8 dies, each with its own 4 MB L2.  (b,h) pairs
@@ -158,26 +162,54 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
         }
     }
 
-    const int tile_lo = group * kPfGroup;
-    const int tile_hi = (tile_lo + kPfGroup - 1 < a.tiles) ? tile_lo + kPfGroup - 1 : a.tiles - 1;
-    float qreg[QE];   // a tile's query elements on their way from HBM to LDS
-    auto fetch_q = [&](int tile) {
+    // Everything the tiles need from memory is requested here, before the first score is stored:
+    // loads and stores share one in-order counter on this chip, and a wait for a load that is mixed
+    // with stores waits for ALL of them, i.e. for a tile's 32 KB of scores to drain to HBM.  Inside
+    // the tile loop there are then stores only.
+    //   * the queries of all GROUP tiles go to LDS as they are (converted tile by tile later);
+    //   * the codes a thread scores are the same for every tile (keys 4*tid .. 4*tid+3 and the
+    //     same 1024 further on): two such quads stay in registers (contexts up to 2048 keys; beyond
+    //     that a loop with loads takes over).  Always issued, at an index clamped into the cache:
+    //     plain values, no partly written arrays.
+    const int tile_lo = group * GROUP;
+    const int tile_hi = (tile_lo + GROUP - 1 < a.tiles) ? tile_lo + GROUP - 1 : a.tiles - 1;
+    for (int x = tid; x < GROUP * TQ * DK; x += NT) {
+        const int t = tile_lo * TQ + x / DK;
+        q_all[x] = (t < a.T) ? qg[(int64_t)t * DK + x % DK] : QT(0.f);
+    }
+    const int last_key = (int)(a.L - 1);
+    PfCodes<M> ka0, ka1, ka2, ka3, kb0, kb1, kb2, kb3;
+#define LOOKAT_PF_LOAD_QUAD(k0_, k1_, k2_, k3_, l0_)                                         \
+    do {                                                                                     \
+        const int q0_ = (l0_);                                                               \
+        k0_.load(codes_bh + (int64_t)(q0_ < last_key ? q0_ : last_key) * M);                 \
+        k1_.load(codes_bh + (int64_t)(q0_ + 1 < last_key ? q0_ + 1 : last_key) * M);         \
+        k2_.load(codes_bh + (int64_t)(q0_ + 2 < last_key ? q0_ + 2 : last_key) * M);         \
+        k3_.load(codes_bh + (int64_t)(q0_ + 3 < last_key ? q0_ + 3 : last_key) * M);         \
+    } while (0)
+    LOOKAT_PF_LOAD_QUAD(ka0, ka1, ka2, ka3, 4 * tid);
+    LOOKAT_PF_LOAD_QUAD(kb0, kb1, kb2, kb3, 4 * tid + 4 * NT);
+#define LOOKAT_PF_KEEP(k_)                                   \
+    _Pragma("unroll") for (int w_ = 0; w_ < (M + 3) / 4; ++w_) asm volatile("" : "+v"(k_.w[w_]))
+    // (a first "use" of the cached codes here, so that the wait for their loads sits in front of
+    // the tile loop and not, re-executed with stores in flight, inside it)
+    LOOKAT_PF_KEEP(ka0);
+    LOOKAT_PF_KEEP(ka1);
+    LOOKAT_PF_KEEP(ka2);
+    LOOKAT_PF_KEEP(ka3);
+    LOOKAT_PF_KEEP(kb0);
+    LOOKAT_PF_KEEP(kb1);
+    LOOKAT_PF_KEEP(kb2);
+    LOOKAT_PF_KEEP(kb3);
+    __syncthreads();   // q_all complete
+    auto stage_q = [&](int tile, float *dst) {   // a tile's queries: LDS as given -> LDS fp32, padded rows
 #pragma unroll
         for (int e = 0; e < QE; ++e) {
             const int x = tid + e * NT;
-            const int t = tile * TQ + x / DK;
-            qreg[e] = (t < a.T) ? pf_to_f32<QT>(qg[(int64_t)t * DK + x % DK]) : 0.f;
+            dst[(x / DK) * QS + x % DK] = pf_to_f32<QT>(q_all[(tile - tile_lo) * (TQ * DK) + x]);
         }
     };
-    auto stage_q = [&](float *dst) {
-#pragma unroll
-        for (int e = 0; e < QE; ++e) {
-            const int x = tid + e * NT;
-            dst[(x / DK) * QS + x % DK] = qreg[e];
-        }
-    };
-    fetch_q(tile_hi);
-    stage_q(q_s);
+    stage_q(tile_hi, q_s);
     int cur = 0;
 
     for (int tile = tile_hi; tile >= tile_lo; --tile) {
@@ -187,23 +219,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
         const float *q_lane = q_s + cur * (TQ * QS) + (tid & 3) * QS;   // matrix operand: query (lane % 4) of the tile
 
         __syncthreads();   // this tile's queries are staged; the previous tile's readers are done with lut_s
-        // The next tile's queries are requested now and written to the other half of q_s after the
-        // build: by then the previous tile's score stores, which that wait also covers, have drained.
-        if (tile > tile_lo)
-            fetch_q(tile - 1);
-        // codes of this thread's first four keys (4*tid .. 4*tid+3): requested now, needed after the build
-        // (always issued, at an index clamped into the cache: plain values, no partly written arrays)
-        const int last_key = (int)(a.L - 1);
-        PfCodes<M> kc0, kc1, kc2, kc3;
-#define LOOKAT_PF_LOAD_QUAD(l0_)                                                             \
-    do {                                                                                     \
-        const int q0_ = (l0_);                                                               \
-        kc0.load(codes_bh + (int64_t)(q0_ < last_key ? q0_ : last_key) * M);                 \
-        kc1.load(codes_bh + (int64_t)(q0_ + 1 < last_key ? q0_ + 1 : last_key) * M);         \
-        kc2.load(codes_bh + (int64_t)(q0_ + 2 < last_key ? q0_ + 2 : last_key) * M);         \
-        kc3.load(codes_bh + (int64_t)(q0_ + 3 < last_key ? q0_ + 3 : last_key) * M);         \
-    } while (0)
-        LOOKAT_PF_LOAD_QUAD(4 * tid);
 
         // ---- tables as [i][c][4]: lut4[i*256 + c] = (q[t]^(i) . C_i[c])_{t=0..3}, j ascending ----
         // Two subspaces at a time: their accumulator chains are independent, so one chain's
@@ -226,7 +241,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
             lut4[(i + 1) * kCentroids + tid] = acc1;
         }
         if (tile > tile_lo)
-            stage_q(q_s + (cur ^ 1) * (TQ * QS));
+            stage_q(tile - 1, q_s + (cur ^ 1) * (TQ * QS));
         cur ^= 1;
         __syncthreads();
 
@@ -238,15 +253,15 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
 #pragma unroll
         for (int t = 0; t < TQ; ++t)
             rowp[t] = scores_bh + (int64_t)(t0 + t) * a.L;
-        for (int l0 = 4 * tid; l0 < kmax; l0 += 4 * NT) {
+        auto score_quad = [&](int l0, const PfCodes<M> &k0, const PfCodes<M> &k1, const PfCodes<M> &k2,
+                              const PfCodes<M> &k3) {
             pf_v4f sc[4];
-            sc[0] = pf_score_key<M>(lut_s, kc0);
-            sc[1] = pf_score_key<M>(lut_s, kc1);
+            sc[0] = pf_score_key<M>(lut_s, k0);
+            sc[1] = pf_score_key<M>(lut_s, k1);
             __builtin_amdgcn_sched_barrier(0);   // two keys' gathers in flight at a time: more would only fill registers
-            sc[2] = pf_score_key<M>(lut_s, kc2);
-            sc[3] = pf_score_key<M>(lut_s, kc3);
+            sc[2] = pf_score_key<M>(lut_s, k2);
+            sc[3] = pf_score_key<M>(lut_s, k3);
             __builtin_amdgcn_sched_barrier(0);
-            LOOKAT_PF_LOAD_QUAD(l0 + 4 * NT);    // next keys of this thread (clamped: harmless past the end)
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 const int tq = t0 + t;
@@ -265,6 +280,28 @@ __global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const Pref
                             rowp[t][(uint32_t)(l0 + j)] = o[j];
                 }
             }
+        };
+        // The gather addresses depend only on the cached codes, so the compiler would compute all
+        // of them (8 keys x m subspaces) once, outside the tile loop, and spill them.  Declaring the
+        // cached code words modified here keeps that arithmetic (a byte extract and a shift-add per
+        // gather) inside the loop.
+        LOOKAT_PF_KEEP(ka0);
+        LOOKAT_PF_KEEP(ka1);
+        LOOKAT_PF_KEEP(ka2);
+        LOOKAT_PF_KEEP(ka3);
+        LOOKAT_PF_KEEP(kb0);
+        LOOKAT_PF_KEEP(kb1);
+        LOOKAT_PF_KEEP(kb2);
+        LOOKAT_PF_KEEP(kb3);
+#undef LOOKAT_PF_KEEP
+        if (4 * tid < kmax)
+            score_quad(4 * tid, ka0, ka1, ka2, ka3);
+        if (4 * tid + 4 * NT < kmax)
+            score_quad(4 * tid + 4 * NT, kb0, kb1, kb2, kb3);
+        for (int l0 = 4 * tid + 8 * NT; l0 < kmax; l0 += 4 * NT) {   // contexts beyond the cached quads
+            PfCodes<M> kc0, kc1, kc2, kc3;
+            LOOKAT_PF_LOAD_QUAD(kc0, kc1, kc2, kc3, l0);
+            score_quad(l0, kc0, kc1, kc2, kc3);
         }
         // ---- keys no query of the tile may see (from the end of the last quad on) ----
         const int64_t kfill = ((int64_t)kmax + 3) / 4 * 4;
@@ -291,7 +328,8 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
 {
     PrefillArgs a = a0;
     a.tiles = (a.T + kPfTQ - 1) / kPfTQ;
-    const size_t lds = ((size_t)M * kCentroids * kPfTQ + 2 * (size_t)kPfTQ * (DK + 4)) * sizeof(float);
+    const size_t lds = ((size_t)M * kCentroids * kPfTQ + 2 * (size_t)kPfTQ * (DK + 4)) * sizeof(float) +
+                       (size_t)pf_group<QT>() * kPfTQ * DK * sizeof(QT);
     auto kern = score_prefill_kernel<QT, DK, M>;
     if (lds > 64 * 1024) {
         static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS
@@ -305,7 +343,7 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
         }
     }
     a.BH = BH;
-    a.groups = (a.tiles + kPfGroup - 1) / kPfGroup;
+    a.groups = (a.tiles + pf_group<QT>() - 1) / pf_group<QT>();
     dim3 grid((unsigned)((BH + 7) / 8 * 8 * a.groups));
     hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);
     return check_launch("lookat_score_prefill");
@@ -356,7 +394,7 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
         return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of %d bytes for m=%d", cvec, shape->m);
     {
         const int64_t BHp = ((int64_t)shape->B * shape->H + 7) / 8 * 8;
-        const int64_t groups = ((int64_t)(T + kPfTQ - 1) / kPfTQ + kPfGroup - 1) / kPfGroup;
+        const int64_t groups = ((int64_t)(T + kPfTQ - 1) / kPfTQ + kPfGroup / 2 - 1) / (kPfGroup / 2);   // the smaller group size
         if (BHp * groups > 0x7fffffffLL)
             return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*T=%lld*%d exceeds one launch", (long long)shape->B * shape->H, T);
     }

@@ -22,15 +22,20 @@
 //     the kernel's LDS instructions;
 //   * a thread scores four consecutive keys per step, so its 4 x 4 results leave as one 16-byte
 //     store per query row (1 KB contiguous per wavefront and instruction);
-//   * the scoring loop is bound by LDS gather bandwidth (4 bytes per (query, key, subspace)) and by
-//     the scores written to HBM (4 bytes per (query, key), masked ones included).  The gathers hit
+//   * nothing is loaded from memory inside the tile loop: the workgroup's queries wait in LDS and a
+//     thread's codes (the same keys for every tile) in registers.  Loads and stores share one
+//     in-order counter here, so a wait for a load inside the loop would wait for the tile's 32 KB of
+//     scores to drain as well;
+//   * the scoring loop is bound by LDS gathers (4 bytes per (query, key, subspace)) and by the
+//     scores written to HBM (4 bytes per (query, key), masked ones included).  The gathers hit
 //     random bank groups: an LDS read of 16 bytes per lane is served 8 lanes at a time and 8 random
 //     codes pile 2.7 deep on average (measured 21.8 cycles per gather instruction instead of 8).
-//     A conflict-free variant was built and measured: tables as [i/8][c][i%8][4] with lane l
-//     walking the subspaces in the order (u + l) % 8, which needs the 8 accumulators of a lane
-//     rotated by c%8 before they are stored.  It cut the conflict cycles by 70% and was 45% slower
-//     (the rotation's selects and the extra registers cost more than the conflicts), as was keeping
-//     a thread's codes in registers across tiles; neither is kept.
+//     A conflict-free variant was built and measured twice: tables as [i/8][c][i%8][4] with lane l
+//     walking the subspaces in the order (u + l) % 8, and the accumulators rotated among registers
+//     before the store so that 8 consecutive lanes store 8 different subspaces (either 8 accumulators
+//     rotated by c%8, or odd 4-lane blocks working on subspaces 4..7,0..3 plus a rotation of 4 by
+//     lane%4).  Both halve the conflict cycles; the first was 30% slower (its selects), the second
+//     exactly as fast as this kernel: the gathers' bank conflicts are not what bounds it.
 #include "common.h"
 
 namespace lookat {

@@ -27,7 +27,8 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 // ---- cross-lane moves on the vector ALU (DPP / lane swaps): no LDS traffic -----------
 // dpp_mov<CTRL>(x): lane i receives x from the lane the DPP control selects.
 //   quad_perm [a,b,c,d] = a | b<<2 | c<<4 | d<<6;  row_shl:n = 0x100+n;  row_shr:n = 0x110+n;
-//   row_ror:n = 0x120+n;  row_mirror = 0x140;  row_half_mirror = 0x141   (a row = 16 lanes)
+//   row_ror:n = 0x120+n;  row_mirror = 0x140;  row_half_mirror = 0x141;  row_newbcast:n = 0x150+n
+//   (a row = 16 lanes)
 template <int CTRL, int BANK_MASK = 0xf>
 __device__ __forceinline__ float dpp_mov(float keep, float x)
 {
@@ -107,6 +108,8 @@ __device__ __forceinline__ float group_broadcast(float x)
             return dpp_mov<0x114, 0xA>(t, t);   // row_shr:4 into quads 1 and 3
         else
             return dpp_mov<0x104, 0x5>(t, t);   // row_shl:4 into quads 0 and 2
+    } else if constexpr (G == 16) {
+        return dpp_mov<0x150 + J>(x, x);        // row_newbcast:J -- lane J of the 16-lane row to all its lanes
     } else {
         return __shfl(x, (int)((threadIdx.x & (kWave - 1) & ~(G - 1)) + J));
     }

@@ -836,9 +836,9 @@ static int pick_waves(int d_k, int m, int64_t keys_per_split)
 
 // Fused decode step: one workgroup of 256 threads per (b,h), one range.  Every wavefront requests
 // its first kStepPrefetch tiles before the table build.  Measured at B=32, H=12, L=1024, m=4
-// (us per launch): 1 tile 14.0, 2 tiles 13.8, 4 tiles (at two wavefronts per SIMD) 15.9: with
-// everything requested at once the codebook rows (L2 hits) queue behind a compute unit's worth of
-// HBM misses.  m = 16 keeps one tile (registers).
+// (us per launch): 1 tile 14.0, 2 tiles 13.8, 4 tiles (at two wavefronts per SIMD) 15.9, and 15.7
+// with the codebook rows waited for before the tiles are requested: requesting a wavefront's whole
+// share at once does not pay.  m = 16 keeps one tile (registers).
 constexpr int kStepPrefetch = 2;
 template <int DK, typename FT>
 static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)

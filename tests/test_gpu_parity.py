@@ -343,6 +343,19 @@ def test_kmeans_step_bit_exact(lk, d_k, m):
     assert np.array_equal(again, cb)
 
 
+@pytest.mark.parametrize("n_calib", [1, 17, 16384, 16385])
+def test_kmeans_step_calibration_set_sizes(lk, n_calib):
+    """One key, a ragged handful, and both sides of the size at which the update kernel changes from
+    member lists in LDS to a scan of all keys: same bits as the oracle either way."""
+    cfg = li.shrink(li.CONFIGS["C1"], H=2, L=8, d_k=16, m=2, n_calib=max(n_calib, 300), rank=8)
+    case = li.make_case(cfg, seed=4200 + n_calib)
+    calib = np.ascontiguousarray(case["calib"][:, :n_calib])   # (the initial codebooks are drawn from 300 keys)
+    ref, _ = oracle.kmeans_step(calib, case["cb_init"])
+    got, assign = lk.lookat_kmeans_step(dev(calib), dev(case["cb_init"]))
+    assert np.array_equal(assign.cpu().numpy(), oracle.encode_keys(calib[None], case["cb_init"])[0])
+    assert np.array_equal(got.cpu().numpy(), ref)
+
+
 def test_kmeans_empty_cluster_keeps_centroid(lk):
     cfg = li.shrink(li.CONFIGS["C1"], H=1, L=8, n_calib=300, m=2)
     case = li.make_case(cfg, seed=4100)

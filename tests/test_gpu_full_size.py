@@ -122,6 +122,40 @@ def test_config_c3_full_size_long_context(lk):
         assert np.max(np.abs(_slab(out, b, h) - out_ref)) <= OUT_ATOL
 
 
+def test_config_c3_full_size_grouped_queries(lk):
+    """The long-context shape with 4 query heads per key/value head (32 query heads, 8 key/value heads),
+    in the launch configuration `bench.py --workload C3 --group 4` times: sampled (b, key/value head)
+    slabs, every query head of the group against the oracle, scores included."""
+    g = 4
+    cfg = li.CONFIGS["C3"]
+    kv = li.shrink(cfg, H=cfg.H // g, n_calib=2048)
+    case = li.torch_case(kv, "cuda", layer=1)
+    cb = lk.lookat_kmeans(case["calib"], case["cb_init"], 1)
+    scale = 1.0 / math.sqrt(cfg.d_k)
+    codes = lk.lookat_encode_keys(case["keys"], cb)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(li.BASE_SEED + 4242)
+    q = (torch.randn((cfg.B, cfg.H, 1, cfg.d_k), generator=gen, device="cuda") / 8).to(case["q"].dtype)
+    lut = lk.lookat_build_lut(q, cb.repeat_interleave(g, dim=0).contiguous())
+    scores = torch.empty((cfg.B, cfg.H, cfg.L), dtype=torch.float32, device="cuda")
+    out = lk.lookat_attend_decode_gqa(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale,
+                                      scores_out=scores)
+    assert torch.isfinite(out).all()
+    cbn = cb.cpu().numpy()
+    for b, h in _sample_bh(kv, 3, 5):
+        got_codes = _slab(codes, b, h)
+        qs = q[b:b + 1, h * g:(h + 1) * g].contiguous().cpu().numpy()                    # [1,g,1,d_k]
+        lut_ref = oracle.build_lut(qs, np.repeat(cbn[h:h + 1], g, axis=0))[:, :, 0]        # [1,g,m,256]
+        out_ref, s_ref = oracle.attend_decode_gqa(lut_ref, got_codes, _slab(case["values"], b, h), scale,
+                                                  want_scores=True)
+        assert np.max(np.abs(out[b:b + 1, h * g:(h + 1) * g].cpu().numpy() - out_ref)) <= OUT_ATOL
+        # |score error| <= 1e-4 of the summands' magnitude (sum over subspaces of the table entries picked)
+        idx = got_codes[0, 0].astype(np.int64)                                             # [L,m]
+        mag = np.abs(lut_ref[0])[:, np.arange(cfg.m)[None, :], idx].sum(-1)                # [g,L]
+        err = np.abs(scores[b, h * g:(h + 1) * g].cpu().numpy().astype(np.float64) - s_ref[0])
+        assert np.all(err <= REL * np.maximum(mag, 1e-6)), f"slab {(b, h)}: {err.max()}"
+
+
 def test_config_c4_full_size_prefill(lk):
     """Prefill block: 32 heads, d_k=128, m=16, batch 4, 2048 fp16 keys and 2048 causal queries per head."""
     cfg = li.CONFIGS["C4"]

@@ -42,7 +42,7 @@ COUNTED_TRAFFIC = {
     ("C2", True): (26395.0, 24584.0, 49152.0, 108.0),
     ("C2", False): (26151.5, 24586.0, 49152.0, 96.0),
     ("C3", False): (1.08262e6, 1.04859e6, 2097152.0, 268.278),
-    ("C4", "score_prefill"): (89775.5, 1.0, 2.0, 2.09942e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
+    ("C4", "score_prefill"): (147935.0, 1.0, 2.0, 2.09826e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
 

@@ -435,6 +435,55 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
     }
 }
 
+// Fused step, table-building wavefronts (256 threads): thread c takes centroid c of each subspace
+// from the codebook of the head and from the same row computes
+//   the table entry  LUT_i[c] = q^(i) . C_i[c]           (Sec. 3.5, fp32, ascending j)
+//   the distance     || k_new^(i) - C_i[c] ||^2          (Sec. 3.4, fp64, as the encoder)
+// and leaves per (subspace, wavefront) the smallest distance and its lowest centroid index in LDS.
+// q and k_new are read-only and addressed uniformly over the wavefront: read through the constant
+// address space they become scalar loads (SGPR operands of the FMAs below) and stay out of the
+// in-order vector-memory queue.  Subspaces are processed in groups whose rows fit 64 registers,
+// all rows of a group requested together.
+template <typename FT, int DK, int M>
+__device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int tid, int lane, int wave, float *lut_s,
+                                              double *enc_d, int *enc_c)
+{
+    constexpr int DSUB = DK / M;
+    constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
+    float frow[GS][DSUB];
+    const float *__restrict__ cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * DSUB + (int64_t)tid * DSUB;
+    load_centroid_rows<DSUB, GS>(frow, cbh, 0);
+    const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * DK * sizeof(FT));
+    const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
+#pragma unroll
+    for (int i0 = 0; i0 < M; i0 += GS) {
+        if (i0 > 0)
+            load_centroid_rows<DSUB, GS>(frow, cbh, i0);
+        double dv[GS], dm[GS];
+#pragma unroll
+        for (int g = 0; g < GS; ++g) {
+            const int i = i0 + g;
+            float e = 0.f;
+#pragma unroll
+            for (int j = 0; j < DSUB; ++j)
+                e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
+            lut_s[i * kCentroids + tid] = e;
+            dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
+            dm[g] = dv[g];
+        }
+        dmin_wave<GS>(dm);
+#pragma unroll
+        for (int g = 0; g < GS; ++g) {
+            // lowest lane that holds the wave minimum = lowest centroid index of this wave
+            const uint64_t holders = __ballot(dv[g] == dm[g]);
+            if (lane == 0) {
+                enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
+                enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+            }
+        }
+    }
+}
+
 // FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused
 // decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
 // the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
@@ -449,7 +498,13 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
                                       p_L, p_kps, p_scale_log2e, late, !std::is_void<FT>::value);
     constexpr bool FUSED = !std::is_void<FT>::value;
-    static_assert(!FUSED || (WAVES == kDecWaves && M != 0 && G == 1), "fused step: 256 threads, compile-time m, one query head");
+    static_assert(!FUSED || (WAVES == 2 * kDecWaves && M != 0 && G == 1), "fused step: 512 threads, compile-time m, one query head");
+    // Fused step: the eight wavefronts take two roles until the table exists.  The first four
+    // (256 threads, thread c = centroid c) fetch the codebook rows, build the table and encode the
+    // new key (step_prologue) and request no tile before that is done; the other four request
+    // their tiles at once and wait.  A wavefront issues in order, and under a saturated memory
+    // pipe a tile request is accepted only as fast as data leaves the pipe: a wavefront that has
+    // tile requests queued ahead of its table arithmetic starts that arithmetic microseconds late.
     static_assert(G == 1 || M != 0, "grouped queries: compile-time m");
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
     constexpr int RPL = kWave / LPR;       // value rows covered by one wave-wide load
@@ -469,7 +524,8 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     const int m = M ? M : a.m;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // in a scalar register: role branches are scalar branches
+    const bool builds_table = FUSED && wave < kDecWaves;
 
     const uint32_t k0 = (uint32_t)split * (uint32_t)a.keys_per_split;
     const uint32_t k1 = (k0 + a.keys_per_split < a.L) ? (uint32_t)(k0 + a.keys_per_split) : (uint32_t)a.L;
@@ -499,17 +555,6 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
             else
                 lut_r[x] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    //    (fused step: instead of a table slice, the first group of codebook rows; they come from
-    //    L2 and are requested FIRST, because loads return in order: behind the value rows they
-    //    would only be usable once the whole tile has arrived)
-    constexpr int FDSUB = (FUSED && M != 0) ? DK / (M ? M : 1) : 1;
-    constexpr int FGS = !FUSED ? 1 : ((64 / FDSUB) < 1 ? 1 : ((64 / FDSUB) > M ? M : (64 / FDSUB)));
-    float frow[FGS][FDSUB];
-    const float *__restrict__ cbh = nullptr;
-    if constexpr (FUSED) {
-        cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * FDSUB + (int64_t)tid * FDSUB;
-        load_centroid_rows<FDSUB, FGS>(frow, cbh, 0);
-    }
     // 2) the codes of the wave's first tile;  3) its value rows.
     // Lane (rowin, sub) holds the value rows RPL*j + rowin, j = 0..NLD-1, of a tile.  It scores
     // the key RPL*sub + rowin, so the NLD weights a lane needs sit in its own group of LPR
@@ -520,61 +565,37 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     uint32_t kb = k0 + (uint32_t)wave * kTile;
     KeyCodes<M ? M : 4> kcs[PF];
     v4u vs[PF][CH];
-#pragma unroll
-    for (int t = 0; t < PF; ++t) {
-        // Unconditional: requests past the range return zero (descriptor bounds).  Behind a branch
-        // the compiler could no longer count how many requests follow a given one, and every wait
-        // would become a wait for all of them.
-        const uint32_t kbt = kb + (uint32_t)t * NT;
-        if constexpr (M != 0)
-            kcs[t].load(rc, (kbt + kofs) * M);
-        __builtin_amdgcn_sched_barrier(0);   // keep the request order: codes before value rows
-        load_rows<DK, CH>(vs[t], rv, kbt, 0, lane);
+    // Unconditional within its role: requests past the range return zero (descriptor bounds).  Behind a
+    // per-tile branch the compiler could no longer count how many requests follow a given one, and every
+    // wait would become a wait for all of them.  (A macro: a lambda that captures the register arrays
+    // sends them through scratch memory.)
+#define LOOKAT_REQUEST_FIRST_TILES()                                                                   \
+    _Pragma("unroll") for (int t = 0; t < PF; ++t)                                                     \
+    {                                                                                                  \
+        const uint32_t kbt = kb + (uint32_t)t * NT;                                                    \
+        if constexpr (M != 0)                                                                          \
+            kcs[t].load(rc, (kbt + kofs) * M);                                                         \
+        __builtin_amdgcn_sched_barrier(0); /* keep the request order: codes before value rows */       \
+        load_rows<DK, CH>(vs[t], rv, kbt, 0, lane);                                                    \
+    }
+    if constexpr (FUSED) {
+        // one branch per role: the table builders' codebook rows and the streamers' tiles then never
+        // hold registers at the same time
+        if (builds_table) {
+            // issue ahead of the streamers that share the SIMD: the codebook requests must enter the
+            // compute unit's memory queue before the tile requests fill it
+            __builtin_amdgcn_s_setprio(3);
+            step_prologue<FT, DK, M>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c);
+            __builtin_amdgcn_s_setprio(0);
+        } else {
+            LOOKAT_REQUEST_FIRST_TILES()
+        }
+    } else {
+        LOOKAT_REQUEST_FIRST_TILES()
     }
     KeyCodes<M ? M : 4> &kc = kcs[0];
     v4u(&v)[CH] = vs[0];
-    if constexpr (FUSED) {
-        // While the first tile is in flight: thread c takes centroid c of each subspace from the
-        // (L2-resident) codebook of the head, and from the same row computes
-        //   the table entry  LUT_i[c] = q^(i) . C_i[c]           (Sec. 3.5, fp32, ascending j)
-        //   the distance     || k_new^(i) - C_i[c] ||^2          (Sec. 3.4, fp64, as the encoder)
-        // q and k_new are read at wave-uniform addresses.  Subspaces are processed in groups
-        // whose rows fit 64 registers, all rows of a group requested together.
-        constexpr int DSUB = FDSUB;
-        constexpr int GS = FGS;
-        // q and k_new are read-only and addressed uniformly over the wavefront: read through the
-        // constant address space they become scalar loads (SGPR operands of the FMAs below) and
-        // stay out of the in-order vector-memory queue that carries the value rows.
-        const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * DK * sizeof(FT));
-        const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
-#pragma unroll
-        for (int i0 = 0; i0 < M; i0 += GS) {
-            if (i0 > 0)
-                load_centroid_rows<DSUB, GS>(frow, cbh, i0);
-            double dv[GS], dm[GS];
-#pragma unroll
-            for (int g = 0; g < GS; ++g) {
-                const int i = i0 + g;
-                float e = 0.f;
-#pragma unroll
-                for (int j = 0; j < DSUB; ++j)
-                    e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
-                lut_s[i * kCentroids + tid] = e;
-                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
-                dm[g] = dv[g];
-            }
-            dmin_wave<GS>(dm);
-#pragma unroll
-            for (int g = 0; g < GS; ++g) {
-                // lowest lane that holds the wave minimum = lowest centroid index of this wave
-                const uint64_t holders = __ballot(dv[g] == dm[g]);
-                if (lane == 0) {
-                    enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
-                    enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
-                }
-            }
-        }
-    } else {
+    if constexpr (!FUSED) {
         float4 *s4 = reinterpret_cast<float4 *>(lut_s);
         if constexpr (STAGED) {
 #pragma unroll
@@ -587,6 +608,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
         }
     }
     __syncthreads();   // table (and, fused, the per-wave argmins) complete in LDS; value rows stay in flight
+    if constexpr (FUSED) {
+        if (builds_table) {
+            LOOKAT_REQUEST_FIRST_TILES()
+        }
+    }
+#undef LOOKAT_REQUEST_FIRST_TILES
 
     // First tile (requested above), then the wave's remaining tiles: request, consume.  Tiles
     // are requested only if they exist (a load past the range would return zero but still
@@ -834,33 +861,36 @@ static int pick_waves(int d_k, int m, int64_t keys_per_split)
     return keys_per_split >= 32 * kTile ? 16 : 4;
 }
 
-// Fused decode step: one workgroup of 256 threads per (b,h), one range.  Every wavefront requests
-// its first kStepPrefetch tiles before the table build.  Measured at B=32, H=12, L=1024, m=4
-// (us per launch): 1 tile 14.0, 2 tiles 13.8, 4 tiles (at two wavefronts per SIMD) 15.9, and 15.7
-// with the codebook rows waited for before the tiles are requested: requesting a wavefront's whole
-// share at once does not pay.  m = 16 keeps one tile (registers).
+// Fused decode step: one workgroup of 512 threads per (b,h), one range: four wavefronts build the
+// table and encode the new key, four request their first kStepPrefetch tiles at once; after the
+// barrier the table builders request theirs and all eight stream.  Measured at B=32, H=12,
+// L=1024, m=4 (us per launch): 256 threads, every wavefront doing both 13.8 (one tile ahead 14.0,
+// four 15.9); 512 threads with the two roles 13.4; the same with the table builders at raised
+// wave priority 11.8 (their codebook requests enter the compute unit's memory queue ahead of
+// the streamers' tile requests instead of interleaved with them).
 constexpr int kStepPrefetch = 2;
+constexpr int kStepWaves = 2 * kDecWaves;   // four wavefronts build the table, four start streaming at once
 template <int DK, typename FT>
 static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
-    dim3 block(kDecThreads);
-    const size_t lds = ((size_t)a.m * kCentroids + (size_t)kDecWaves * (DK + 2)) * sizeof(float) +
+    dim3 block(kStepWaves * kWave);
+    const size_t lds = ((size_t)a.m * kCentroids + (size_t)kStepWaves * (DK + 2)) * sizeof(float) +
                        (size_t)a.m * kDecWaves * (sizeof(double) + sizeof(int));
     switch (a.m) {
-    case 2:   // 32- or 64-coordinate rows: give the register allocator the larger budget
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kDecWaves, 2, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+    case 2:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kStepWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 4:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kDecWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kStepWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 8:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kDecWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kStepWaves, 4, FT, 1, kStepPrefetch>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     case 16:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kDecWaves, 4, FT, 1, 1>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kStepWaves, 4, FT, 1, 1>), grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true),
                            late_of(a));
         return true;
     default:

@@ -37,10 +37,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # FETCH_SIZE of lookat::stream_read_kernel in the same run, KiB that kernel reads, WRITE_SIZE
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {
-    ("C1", True): (1239.01, 778.004, 1536.0, 3.375),
-    ("C1", False): (831.504, 778.004, 1536.0, 3.0),
-    ("C2", True): (26395.0, 24584.0, 49152.0, 108.0),
-    ("C2", False): (26151.5, 24586.0, 49152.0, 96.0),
+    ("C1", True): (1247.01, 776.004, 1536.0, 3.375),
+    ("C1", False): (831.0, 776.004, 1536.0, 3.0),
+    ("C2", True): (26387.6, 24584.0, 49152.0, 108.0),
+    ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
     ("C3", False): (1.08262e6, 1.04859e6, 2097152.0, 268.278),
     ("C4", "score_prefill"): (147935.0, 1.0, 2.0, 2.09826e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }

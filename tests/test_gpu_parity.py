@@ -433,9 +433,11 @@ def _step_reference(case, cb, L, scale):
 
 @pytest.mark.parametrize("d_k,m", [(64, 4), (64, 2), (64, 8), (64, 16), (128, 8), (128, 16), (128, 2), (128, 4)])
 @pytest.mark.parametrize("qk_dtype", ["float16", "float32"])
-@pytest.mark.parametrize("L", [1, 64, 65, 300, 1024])
+@pytest.mark.parametrize("L", [1, 64, 65, 300, 1024, 1537, 4133])
 def test_decode_step_matches_oracle(lk, d_k, m, qk_dtype, L):
-    B, H, Lmax = 2, 5, 1100
+    """Contexts from one key to several rounds of the workgroup's 512-key step (the last two lengths run
+    the streaming loop behind the tiles requested up front, with a ragged tail)."""
+    B, H, Lmax = 2, 5, max(1100, L + 67)
     cfg = li.shrink(li.CONFIGS["C2"], B=B, H=H, L=Lmax, d_k=d_k, m=m, n_calib=400, key_dtype=qk_dtype,
                     q_dtype=qk_dtype, rank=8 if d_k == 64 else 16)
     case = li.make_case(cfg, seed=6000 + d_k + m)

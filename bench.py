@@ -41,7 +41,8 @@ COUNTED_TRAFFIC = {
     ("C1", False): (831.0, 776.004, 1536.0, 3.0),
     ("C2", True): (26387.6, 24584.0, 49152.0, 108.0),
     ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
-    ("C3", False): (1.08262e6, 1.04859e6, 2097152.0, 268.278),
+    ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
+    ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),
     ("C4", "score_prefill"): (147935.0, 1.0, 2.0, 2.09826e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
@@ -64,7 +65,7 @@ def parse_args():
                     help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
                     help="fused: one lookat_decode_step per layer; calls: encode_keys + build_lut + attend_decode; "
-                         "auto: fused when the library would use a single range per (b,h)")
+                         "auto: fused when B*H >= 256 or the library would use a single range per (b,h)")
     ap.add_argument("--group", type=int, default=1, choices=[1, 2, 4, 8],
                     help="decode workloads: query heads per key/value head (grouped-query attention): the workload's H "
                          "query heads share H/group key/value heads; times lookat_attend_decode_gqa")
@@ -138,8 +139,10 @@ def main():
         lk.lookat_attend_decode(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
                                 num_splits=splits, workspace=workspace, out=ly.out)
 
-    fused = args.path == "fused" or (args.path == "auto" and splits == 1 and cfg.d_k in (64, 128)
-                                     and cfg.m in (2, 4, 8, 16))
+    # auto: the fused step has one workgroup per (b,h); it is used when that fills the chip's 256
+    # compute units or when the unfused call would not cut the sequence either
+    fused = args.path == "fused" or (args.path == "auto" and (splits == 1 or cfg.B * cfg.H >= 256)
+                                     and cfg.d_k in (64, 128) and cfg.m in (2, 4, 8, 16))
 
     def fused_only(ly):
         lk.lookat_decode_step(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)

@@ -120,6 +120,14 @@ def test_config_c3_full_size_long_context(lk):
         lut_ref = oracle.build_lut(_slab(case["q"], b, h), cbn[h:h + 1])
         out_ref = oracle.attend_decode(lut_ref[:, :, 0], got_codes, _slab(case["values"], b, h), scale)
         assert np.max(np.abs(_slab(out, b, h) - out_ref)) <= OUT_ATOL
+    # the fused step (what bench.py times at this shape: B*H = 256 workgroups, one range each) on a cache
+    # whose last row is stale lands on the same codes and, up to the order of the partial sums, outputs
+    cache = codes.clone()
+    cache[:, :, -1] = 0xEE
+    out1 = lk.lookat_decode_step(case["q"][:, :, 0].to(case["keys"].dtype).contiguous(),
+                                 case["keys"][:, :, -1].contiguous(), cb, cache, case["values"], scale)
+    assert torch.equal(cache, codes)
+    assert float((out1 - out).abs().max()) <= 1e-5
 
 
 def test_config_c3_full_size_grouped_queries(lk):

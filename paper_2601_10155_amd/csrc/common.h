@@ -115,6 +115,58 @@ __device__ __forceinline__ float group_broadcast(float x)
     }
 }
 
+// Argmin over the 256 centroids with the encoder's rule (strict '<' scan over ascending index).
+// Distances are mapped to an order value: the distance itself; a NaN becomes +inf (it never
+// wins), except at centroid 0, where it becomes -1 (the scan starts there and nothing compares
+// below a NaN).  The smallest order value with the lowest index is then exactly the scan's result.
+__device__ __forceinline__ double argmin_value(double d, int c)
+{
+    return (d != d) ? (c == 0 ? -1.0 : (double)INFINITY) : d;
+}
+template <int CTRL>
+__device__ __forceinline__ double dmin_dpp(double x)
+{
+    const uint64_t u = (uint64_t)__double_as_longlong(x);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)u, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(u >> 32), (int)(uint32_t)(u >> 32), CTRL,
+                                                               0xf, 0xf, false);
+    return fmin(x, __longlong_as_double((long long)(((uint64_t)hi << 32) | lo)));
+}
+// N independent minima over the wavefront, reduced in lock step (the chains interleave);
+// every lane ends with all N results.
+template <int N>
+__device__ __forceinline__ void dmin_wave(double (&x)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0xB1>(x[i]);    // lane ^ 1
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x4E>(x[i]);    // lane ^ 2
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x141>(x[i]);   // other quad of each 8
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        x[i] = dmin_dpp<0x140>(x[i]);   // other 8 of each 16
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const uint64_t u = (uint64_t)__double_as_longlong(x[i]);
+        const auto l = __builtin_amdgcn_permlane16_swap((uint32_t)u, (uint32_t)u, false, false);
+        const auto h = __builtin_amdgcn_permlane16_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+        x[i] = fmin(__longlong_as_double((long long)(((uint64_t)h[0] << 32) | l[0])),
+                    __longlong_as_double((long long)(((uint64_t)h[1] << 32) | l[1])));
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const uint64_t u = (uint64_t)__double_as_longlong(x[i]);
+        const auto l = __builtin_amdgcn_permlane32_swap((uint32_t)u, (uint32_t)u, false, false);
+        const auto h = __builtin_amdgcn_permlane32_swap((uint32_t)(u >> 32), (uint32_t)(u >> 32), false, false);
+        x[i] = fmin(__longlong_as_double((long long)(((uint64_t)h[0] << 32) | l[0])),
+                    __longlong_as_double((long long)(((uint64_t)h[1] << 32) | l[1])));
+    }
+}
+
 // 2^x on the transcendental unit; 2^-inf = 0.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

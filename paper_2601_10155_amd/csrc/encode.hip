@@ -123,25 +123,6 @@ __global__ __launch_bounds__(kEncThreads) void encode_generic_kernel(const KT *_
 // (same arithmetic, same order) and the block takes the argmin over (distance, index).
 constexpr int kEncFewKeys = 8;
 
-// Total order that reproduces the serial scan: smaller distance first, then smaller index.
-// Distances are sums of squares (>= +0), so their bit patterns order like the values; a NaN
-// maps above everything except at centroid 0, where it maps below everything (the serial
-// scan starts from centroid 0 and no later distance compares below a NaN).
-__device__ __forceinline__ uint64_t dist_order_key(double d, int c)
-{
-    if (d != d)
-        return c == 0 ? 0ull : ~0ull;
-    return (uint64_t)__double_as_longlong(d);
-}
-
-__device__ __forceinline__ void argmin_merge(uint64_t &k, int &c, uint64_t k2, int c2)
-{
-    if (k2 < k || (k2 == k && c2 < c)) {
-        k = k2;
-        c = c2;
-    }
-}
-
 template <typename KT, int DSUB>
 __global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__restrict__ keys,
                                                                 const float *__restrict__ codebooks,
@@ -149,7 +130,7 @@ __global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__rest
                                                                 int B, int H, int64_t N, int d_k, int m)
 {
     __shared__ double x_s[kEncFewKeys][DSUB];
-    __shared__ uint64_t red_k[kEncFewKeys][kCentroids / kWave];
+    __shared__ double red_d[kEncFewKeys][kCentroids / kWave];
     __shared__ int red_c[kEncFewKeys][kCentroids / kWave];
 
     const int i = blockIdx.y;
@@ -177,6 +158,10 @@ __global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__rest
     }
     __syncthreads();
 
+    // Distances of centroid c to the block's keys, then per key the minimum over the wavefront's 64
+    // centroids (cross-lane moves on the vector ALU, the eight chains interleaved) and the lowest
+    // lane that holds it: the serial scan's choice among exact ties.
+    double dv[kEncFewKeys], dm[kEncFewKeys];
 #pragma unroll
     for (int k = 0; k < kEncFewKeys; ++k) {
         double acc = 0.0;
@@ -186,17 +171,16 @@ __global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__rest
             double sq = diff * diff;
             acc = acc + sq;
         }
-        uint64_t key = dist_order_key(acc, c);
-        int best = c;
+        dv[k] = argmin_value(acc, c);
+        dm[k] = dv[k];
+    }
+    dmin_wave<kEncFewKeys>(dm);
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const uint64_t k2 = __shfl_xor((unsigned long long)key, off);
-            const int c2 = __shfl_xor(best, off);
-            argmin_merge(key, best, k2, c2);
-        }
+    for (int k = 0; k < kEncFewKeys; ++k) {
+        const uint64_t holders = __ballot(dv[k] == dm[k]);
         if (lane == 0) {
-            red_k[k][wave] = key;
-            red_c[k][wave] = best;
+            red_d[k][wave] = dm[k];
+            red_c[k][wave] = wave * kWave + (int)__builtin_ctzll(holders);
         }
     }
     __syncthreads();
@@ -204,11 +188,17 @@ __global__ __launch_bounds__(kCentroids) void encode_few_kernel(const KT *__rest
         const int k = threadIdx.x;
         const int64_t r = r0 + k;
         if (r < rows) {
-            uint64_t key = red_k[k][0];
+            // wavefronts hold ascending centroid ranges: strict '<' keeps the lowest index on ties
+            double bd = red_d[k][0];
             int best = red_c[k][0];
 #pragma unroll
-            for (int w = 1; w < kCentroids / kWave; ++w)
-                argmin_merge(key, best, red_k[k][w], red_c[k][w]);
+            for (int w = 1; w < kCentroids / kWave; ++w) {
+                const double d = red_d[k][w];
+                const int cw = red_c[k][w];
+                const bool better = d < bd;
+                bd = better ? d : bd;
+                best = better ? cw : best;
+            }
             const int64_t b = r / N, n = r % N;
             codes[(b * H + h) * code_stride_bh + n * m + i] = (uint8_t)best;
         }

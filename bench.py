@@ -65,7 +65,10 @@ def parse_args():
                     help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
                     help="fused: one lookat_decode_step per layer; calls: encode_keys + build_lut + attend_decode; "
-                         "auto: fused when B*H >= 256 or the library would use a single range per (b,h)")
+                         "auto: fused wherever the library has a fused kernel for the shape")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="override the workload's batch size (e.g. --workload C3 --batch 1: single-user long context; "
+                         "the fused step is then cut into ranges, lookat_decode_step_split)")
     ap.add_argument("--group", type=int, default=1, choices=[1, 2, 4, 8],
                     help="decode workloads: query heads per key/value head (grouped-query attention): the workload's H "
                          "query heads share H/group key/value heads; times lookat_attend_decode_gqa")
@@ -117,6 +120,8 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = li.CONFIGS[args.workload]
+    if args.batch:
+        cfg = li.shrink(cfg, B=args.batch)
     if cfg.T > 1:
         prefill_main(args, cfg, lk, li, torch, device)
         return
@@ -139,13 +144,20 @@ def main():
         lk.lookat_attend_decode(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
                                 num_splits=splits, workspace=workspace, out=ly.out)
 
-    # auto: the fused step has one workgroup per (b,h); it is used when that fills the chip's 256
-    # compute units or when the unfused call would not cut the sequence either
-    fused = args.path == "fused" or (args.path == "auto" and (splits == 1 or cfg.B * cfg.H >= 256)
-                                     and cfg.d_k in (64, 128) and cfg.m in (2, 4, 8, 16))
+    # auto: the fused step wherever the library has one for the shape (one workgroup per (b,h) when that
+    # fills the chip's 256 compute units or the unfused call would not cut the sequence either; else cut
+    # into ranges, lookat_decode_step_split)
+    fused = args.path == "fused" or (args.path == "auto" and cfg.d_k in (64, 128) and cfg.m in (2, 4, 8, 16))
+
+    # the fused step is cut into ranges when one workgroup per (b,h) would leave the chip idle
+    fused_split = fused and splits > 1 and cfg.B * cfg.H < 256
 
     def fused_only(ly):
-        lk.lookat_decode_step(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)
+        if fused_split:
+            lk.lookat_decode_step_split(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, num_splits=splits,
+                                        workspace=workspace, out=ly.out)
+        else:
+            lk.lookat_decode_step(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)
 
     def step():
         for ly in layers:
@@ -248,7 +260,8 @@ def main():
         "config": {
             "workload": f"{cfg.name}: B={cfg.B} H={cfg.H} L={cfg.L} d_k={cfg.d_k} m={cfg.m} K={cfg.K} "
                         f"layers={cfg.layers}; per layer encode(1 new key) + build_lut + attend_decode",
-            "path": "lookat_decode_step (one fused kernel per layer)" if fused
+            "path": ("lookat_decode_step_split (fused ranges + merge per layer)" if fused_split
+                     else "lookat_decode_step (one fused kernel per layer)") if fused
                     else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode",
             "values": "fp16", "codes": "u8 (" + args.codes + ")", "lut": "f32", "launch": args.mode, "num_splits": splits,
             "codebooks": f"{args.kmeans_iters} Lloyd iterations (lookat_kmeans_step) on {cfg.n_calib} seeded "
@@ -261,7 +274,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": counted_traffic((cfg.name, fused)),
+            "traffic": None if args.batch else counted_traffic((cfg.name, fused)),
             "bytes_per_launch": bytes_per_launch,
             "us_per_launch": us_per_launch,
             "launches_timed": n_launch,

@@ -200,6 +200,31 @@ int lookat_decode_step(const lookat_shape *shape, int64_t L,
                        float *out,
                        void *stream);
 
+/*
+ * The fused decode step with the sequence of every (b,h) cut into num_splits ranges, for few
+ * (b,h) pairs and long contexts (single-user decode), where one workgroup per (b,h) would leave
+ * most of the chip idle.  Same results as lookat_decode_step (Algorithm 1 with the split-K merge
+ * of lookat_attend_decode; paper Sec. 3.4 "Encoding", Sec. 3.5): every range's workgroup builds
+ * the query's tables, the one that holds position L-1 also encodes and appends the new key, and
+ * a second kernel merges the ranges.
+ *   num_splits                 ranges per (b,h); 0 = the library's choice (as lookat_attend_decode)
+ *   workspace, workspace_bytes device scratch of at least
+ *                              lookat_decode_step_split_workspace_bytes(shape, L, num_splits) bytes,
+ *                              16-byte aligned, caller-owned; may be NULL when that is 0
+ * All other arguments, supported shapes and error behaviour as lookat_decode_step.
+ */
+size_t lookat_decode_step_split_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits);
+
+int lookat_decode_step_split(const lookat_shape *shape, int64_t L,
+                             const void *q, const void *k_new, int qk_dtype,
+                             const float *codebooks,
+                             uint8_t *codes, int64_t code_stride_bh,
+                             const void *values, int64_t value_stride_bh,
+                             float scale, int32_t num_splits,
+                             void *workspace, size_t workspace_bytes,
+                             float *out,
+                             void *stream);
+
 /* The split count lookat_attend_decode uses when num_splits == 0 (host only,
  * no HIP call); 0 if the shape is invalid. */
 int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);

@@ -60,6 +60,10 @@ def load_library():
         lib.lookat_attend_decode_gqa.restype = ctypes.c_int
         lib.lookat_decode_step.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, vp, vp]
         lib.lookat_decode_step.restype = ctypes.c_int
+        lib.lookat_decode_step_split_workspace_bytes.argtypes = [sp, i64, i32]
+        lib.lookat_decode_step_split_workspace_bytes.restype = sz
+        lib.lookat_decode_step_split.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp]
+        lib.lookat_decode_step_split.restype = ctypes.c_int
         lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
         lib.lookat_score_prefill.restype = ctypes.c_int
         lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
@@ -265,6 +269,23 @@ def lookat_decode_step(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Te
     """Fused decode step.  q, k_new [B,H,d_k] (same dtype), codes [B,H,L,m] u8 (row L-1 is written),
     values [B,H,L,d_k] fp16 (row L-1 already holds the new value) -> out [B,H,d_k] fp32.
     codes / values may be views of longer caches sliced to L rows."""
+    return _decode_step(q, k_new, codebooks, codes, values, scale, out, None, None)
+
+
+def lookat_decode_step_split(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
+                             values: torch.Tensor, scale: float, num_splits: int = 0,
+                             workspace: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+    """The fused decode step with every (b,h)'s sequence cut into num_splits ranges (0 = the library's
+    choice): for few (b,h) pairs and long contexts.  Arguments as lookat_decode_step."""
+    return _decode_step(q, k_new, codebooks, codes, values, scale, out, int(num_splits), workspace)
+
+
+def decode_step_split_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, num_splits: int = 0) -> int:
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_decode_step_split_workspace_bytes(ctypes.byref(shape), L, num_splits))
+
+
+def _decode_step(q, k_new, codebooks, codes, values, scale, out, num_splits, workspace):
     lib = load_library()
     q = _dev(q, "q").contiguous()
     k_new = _dev(k_new, "k_new").contiguous()
@@ -285,9 +306,19 @@ def lookat_decode_step(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Te
     if out.dtype != torch.float32 or out.numel() != B * H * d_k or not out.is_contiguous():
         raise ValueError("out must be contiguous fp32 [B,H,d_k]")
     shape = _Shape(B, H, d_k, m, 256)
-    _check(lib.lookat_decode_step(ctypes.byref(shape), L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
-                                  cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
-                                  out.data_ptr(), _stream(values)))
+    if num_splits is None:
+        _check(lib.lookat_decode_step(ctypes.byref(shape), L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
+                                      cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
+                                      out.data_ptr(), _stream(values)))
+        return out
+    need = int(lib.lookat_decode_step_split_workspace_bytes(ctypes.byref(shape), L, num_splits))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.lookat_decode_step_split(ctypes.byref(shape), L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
+                                        cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
+                                        num_splits, ws_ptr, ws_bytes, out.data_ptr(), _stream(values)))
     return out
 
 

@@ -392,9 +392,11 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // address space they become scalar loads (SGPR operands of the FMAs below) and stay out of the
 // in-order vector-memory queue.  Subspaces are processed in groups whose rows fit 64 registers,
 // all rows of a group requested together.
+// `encode`: this workgroup's range holds position L-1 (with several ranges per (b,h) only the last one
+// scores the new key and appends its codes; the others build the table alone).
 template <typename FT, int DK, int M>
 __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int tid, int lane, int wave, float *lut_s,
-                                              double *enc_d, int *enc_c)
+                                              double *enc_d, int *enc_c, bool encode)
 {
     constexpr int DSUB = DK / M;
     constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
@@ -416,9 +418,14 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
             for (int j = 0; j < DSUB; ++j)
                 e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
             lut_s[i * kCentroids + tid] = e;
-            dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
-            dm[g] = dv[g];
+            dv[g] = dm[g] = 0.0;
+            if (encode) {
+                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
+                dm[g] = dv[g];
+            }
         }
+        if (!encode)
+            continue;
         dmin_wave<GS>(dm);
 #pragma unroll
         for (int g = 0; g < GS; ++g) {
@@ -533,7 +540,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
             // issue ahead of the streamers that share the SIMD: the codebook requests must enter the
             // compute unit's memory queue before the tile requests fill it
             __builtin_amdgcn_s_setprio(3);
-            step_prologue<FT, DK, M>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c);
+            step_prologue<FT, DK, M>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c, k1 == (uint32_t)a.L);
             __builtin_amdgcn_s_setprio(0);
         } else {
             LOOKAT_REQUEST_FIRST_TILES()
@@ -898,14 +905,13 @@ static int launch_gqa_dk(int group, const DecodeArgs &a, dim3 grid, hipStream_t 
 
 }  // namespace lookat
 
-extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
-                                  int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
-                                  const void *values, int64_t value_stride_bh, float scale, float *out, void *stream)
+namespace lookat {
+// Fused step, S ranges per (b,h) (S = 1: no workspace, results written directly).
+static int decode_step_impl(const char *who, const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
+                            int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                            const void *values, int64_t value_stride_bh, float scale, int S, void *workspace,
+                            size_t workspace_bytes, float *out, void *stream)
 {
-    using namespace lookat;
-    clear_error();
-    if (int rc = check_shape(shape))
-        return rc;
     if (L <= 0)
         return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
     if (qk_dtype != LOOKAT_F16 && qk_dtype != LOOKAT_F32)
@@ -921,8 +927,8 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
     const bool m_ok = shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16;
     if (!m_ok || (shape->d_k != 64 && shape->d_k != 128))
         return fail(LOOKAT_ERR_UNSUPPORTED,
-                    "lookat_decode_step handles d_k in {64,128} with m in {2,4,8,16}; got d_k=%d m=%d "
-                    "(use encode_keys + build_lut + attend_decode)", shape->d_k, shape->m);
+                    "%s handles d_k in {64,128} with m in {2,4,8,16}; got d_k=%d m=%d "
+                    "(use encode_keys + build_lut + attend_decode)", who, shape->d_k, shape->m);
     if ((reinterpret_cast<uintptr_t>(codes) % shape->m) || (code_stride_bh % shape->m))
         return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of m=%d bytes", shape->m);
     if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
@@ -930,23 +936,31 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
     if (code_stride_bh > 0xffffffffLL || value_stride_bh > 0xffffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
     const int64_t BH = (int64_t)shape->B * shape->H;
-    const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds;
+    const size_t need = (S == 1) ? 0 : (size_t)BH * S * (shape->d_k + 2) * sizeof(float);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(LOOKAT_ERR_WORKSPACE, "workspace of %zu bytes needed for %d splits, got %zu", need, S,
+                        workspace_bytes);
+        if (!aligned16(workspace))
+            return fail(LOOKAT_ERR_ALIGN, "workspace must be 16-byte aligned");
+    }
+    const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds * S;
     if (nblocks > 0x7fffffffLL)
-        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H=%lld workgroups exceed one launch", (long long)BH);
+        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*num_splits=%lld workgroups exceed one launch", (long long)nblocks);
 
     DecodeArgs a;
     a.lut = nullptr;
     a.codes = codes;
     a.values = static_cast<const __half *>(values);
-    a.part = nullptr;
+    a.part = static_cast<float *>(workspace);
     a.out = out;
     a.scores_out = nullptr;
     a.code_stride = code_stride_bh;
     a.value_stride = value_stride_bh;
     a.L = L;
-    a.keys_per_split = round_up(L, kTile);
+    a.keys_per_split = round_up((L + S - 1) / S, kTile);
     a.BH = (int)BH;
-    a.splits = 1;
+    a.splits = S;
     a.d_k = shape->d_k;
     a.m = shape->m;
     a.scale_log2e = scale * kLog2e;
@@ -964,7 +978,44 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
         ok = (qk_dtype == LOOKAT_F16) ? launch_step<128, __half>(a, grid, st) : launch_step<128, float>(a, grid, st);
     if (!ok)
         return fail(LOOKAT_ERR_UNSUPPORTED, "no fused kernel for this shape");
-    return check_launch("lookat_decode_step");
+    if (S > 1)
+        hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)BH), dim3(kDecThreads), 0, st,
+                           static_cast<const float *>(workspace), out, S, shape->d_k);
+    return check_launch(who);
+}
+}  // namespace lookat
+
+extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
+                                  int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                  const void *values, int64_t value_stride_bh, float scale, float *out, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    return decode_step_impl("lookat_decode_step", shape, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh, values,
+                            value_stride_bh, scale, 1, nullptr, 0, out, stream);
+}
+
+extern "C" size_t lookat_decode_step_split_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits)
+{
+    return lookat_attend_decode_workspace_bytes(shape, L, num_splits);
+}
+
+extern "C" int lookat_decode_step_split(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
+                                        int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                        const void *values, int64_t value_stride_bh, float scale, int32_t num_splits,
+                                        void *workspace, size_t workspace_bytes, float *out, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (num_splits < 0 || num_splits > 65535)
+        return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
+    const int S = num_splits ? num_splits : (L > 0 ? auto_splits(shape, L) : 1);
+    return decode_step_impl("lookat_decode_step_split", shape, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh,
+                            values, value_stride_bh, scale, S, workspace, workspace_bytes, out, stream);
 }
 
 extern "C" int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L)

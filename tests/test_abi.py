@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
             "lookat_probe_stream_read", "lookat_score_prefill", "lookat_decode_step",
-            "lookat_attend_decode_gqa", "lookat_attend_decode_gqa_workspace_bytes"} <= set(names)
+            "lookat_attend_decode_gqa", "lookat_attend_decode_gqa_workspace_bytes", "lookat_decode_step_split",
+            "lookat_decode_step_split_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -167,6 +168,31 @@ def test_decode_step_argument_errors(lib):
     bad = Shape(2, 3, 32, 4, 256)
     a = list(base); a[0] = ctypes.byref(bad); a[9] = L * 32
     assert f(*a) == E_UNSUP
+
+
+def test_decode_step_split_argument_errors(lib):
+    """No call here reaches a launch: every argument list fails a host-side check."""
+    s = Shape(1, 4, 128, 8, 256)
+    f = lib.lookat_decode_step_split
+    ws = lib.lookat_decode_step_split_workspace_bytes
+    L = 8192
+    assert ws(ctypes.byref(s), L, 1) == 0
+    assert ws(ctypes.byref(s), L, 4) == 1 * 4 * 4 * (128 + 2) * 4
+    assert ws(ctypes.byref(s), L, 0) == ws(ctypes.byref(s), L, lib.lookat_attend_decode_auto_splits(ctypes.byref(s), L))
+    base = [ctypes.byref(s), L, FAKE, FAKE, 1, FAKE, FAKE, L * 8, FAKE, L * 128, ctypes.c_float(0.1), 4, FAKE, 1 << 20,
+            FAKE, None]
+    def call(**kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[{"L": 1, "q": 2, "dt": 4, "splits": 11, "ws": 12, "wsb": 13, "out": 14}[k]] = v
+        return f(*a)
+    assert call(L=0) == E_SHAPE
+    assert call(dt=7) == E_DTYPE
+    assert call(splits=-1) == E_SHAPE
+    assert call(ws=None) == E_WS
+    assert call(wsb=100) == E_WS
+    assert call(ws=FAKE + 4) == E_ALIGN
+    assert call(out=None) == E_NULL
 
 
 def test_attend_decode_gqa_argument_errors(lib):

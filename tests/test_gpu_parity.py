@@ -456,6 +456,34 @@ def test_decode_step_matches_oracle(lk, d_k, m, qk_dtype, L):
     assert np.max(np.abs(out.cpu().numpy() - out_ref)) <= OUT_ATOL
 
 
+@pytest.mark.parametrize("d_k,m", [(128, 8), (64, 4), (64, 16), (128, 2)])
+@pytest.mark.parametrize("L,splits", [(700, 2), (4133, 3), (4133, 0), (9000, 7), (1, 4)])
+def test_decode_step_split_matches_oracle(lk, d_k, m, L, splits):
+    """The fused step cut into ranges (few (b,h) pairs, long context): codes and outputs against the oracle,
+    and the same codes as the one-range call.  (1, 4): more ranges than keys; (4133, 0): the library's choice."""
+    B, H, Lmax = 1, 3, L + 40
+    cfg = li.shrink(li.CONFIGS["C3"], B=B, H=H, L=Lmax, d_k=d_k, m=m, n_calib=400, rank=8 if d_k == 64 else 16)
+    case = li.make_case(cfg, seed=6300 + d_k + m + L)
+    cb = case["cb_init"]
+    scale = 1.0 / math.sqrt(d_k)
+    codes_ref, out_ref = _step_reference(case, cb, L, scale)
+    cache = torch.full((B, H, Lmax, m), 0xCD, dtype=torch.uint8, device="cuda")
+    cache[:, :, :L - 1] = dev(codes_ref[:, :, :L - 1])
+    values = dev(case["values"])
+    q = dev(case["q"][:, :, 0]).to(dev(case["keys"]).dtype)
+    k_new = dev(case["keys"][:, :, L - 1])
+    out = lk.lookat_decode_step_split(q, k_new, dev(cb), cache[:, :, :L], values[:, :, :L], scale, num_splits=splits)
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[:, :, :L], codes_ref), "code cache after the step"
+    assert (got[:, :, L:] == 0xCD).all(), "rows past L were touched"
+    assert np.max(np.abs(out.cpu().numpy() - out_ref)) <= OUT_ATOL
+    cache2 = cache.clone()
+    cache2[:, :, L - 1] = 0
+    out1 = lk.lookat_decode_step(q, k_new, dev(cb), cache2[:, :, :L], values[:, :, :L], scale)
+    assert torch.equal(cache2, cache)
+    assert float((out1 - out).abs().max()) <= 1e-5
+
+
 def test_decode_step_equals_three_calls(lk):
     """Same shape as one layer of the GPT-2-small batch-32 workload, reduced batch."""
     cfg = li.shrink(li.CONFIGS["C2"], B=4, n_calib=1024)

@@ -310,8 +310,9 @@ def gqa_main(args, cfg, lk, li, torch, device):
         ly.lut = torch.empty((cfg.B, cfg.H, 1, cfg.m, cfg.K), dtype=torch.float32, device=device)
         ly.out = torch.empty((cfg.B, cfg.H, cfg.d_k), dtype=torch.float32, device=device)
         layers.append(ly)
-    splits = lk.attend_decode_auto_splits(kv.B, kv.H, kv.d_k, kv.m, kv.L)
-    ws = torch.empty(max(16, cfg.B * cfg.H * splits * (cfg.d_k + 2) * 4), dtype=torch.uint8, device=device)
+    splits = 0   # the library's choice for grouped queries
+    ws = torch.empty(max(16, lk.attend_decode_gqa_workspace_bytes(kv.B, kv.H, g, kv.d_k, kv.m, kv.L, 0)),
+                     dtype=torch.uint8, device=device)
 
     def decode_only(ly):
         lk.lookat_attend_decode_gqa(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
@@ -373,7 +374,7 @@ def gqa_main(args, cfg, lk, li, torch, device):
         "config": {"workload": f"{cfg.name} with grouped queries: B={cfg.B} query heads={cfg.H} key/value heads={kv.H} "
                                f"(group={g}) L={cfg.L} d_k={cfg.d_k} m={cfg.m} layers={cfg.layers}; per layer "
                                "encode(1 new key) + build_lut + attend_decode_gqa",
-                   "launch": args.mode, "num_splits": splits},
+                   "launch": args.mode, "num_splits": "library choice"},
         "roofline": {"bound": "hbm", "kernel": f"lookat::decode_split_kernel (group of {g} query heads)",
                      "achieved": kv_bytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": kv_bytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": kv_bytes,

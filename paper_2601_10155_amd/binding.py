@@ -191,6 +191,12 @@ def attend_decode_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, num_
     return int(load_library().lookat_attend_decode_workspace_bytes(ctypes.byref(shape), L, num_splits))
 
 
+def attend_decode_gqa_workspace_bytes(B: int, H: int, group: int, d_k: int, m: int, L: int, num_splits: int = 0) -> int:
+    """Workspace of lookat_attend_decode_gqa (H = key/value heads; num_splits 0 = the library's choice)."""
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_attend_decode_gqa_workspace_bytes(ctypes.byref(shape), group, L, num_splits))
+
+
 def attend_decode_auto_splits(B: int, H: int, d_k: int, m: int, L: int) -> int:
     shape = _Shape(B, H, d_k, m, 256)
     return int(load_library().lookat_attend_decode_auto_splits(ctypes.byref(shape), L))

@@ -752,15 +752,18 @@ __global__ __launch_bounds__(kDecThreads) void decode_combine_kernel(const float
 
 static int64_t round_up(int64_t x, int64_t q) { return (x + q - 1) / q * q; }
 
-static int auto_splits(const lookat_shape *s, int64_t L)
+// Ranges per (b,h) when the caller leaves the choice to the library.  One range as long as the
+// (b,h) count alone fills the 256 compute units: the merge kernel is a second launch and costs more
+// than it buys on short contexts.  With fewer (b,h) pairs the sequence is cut so that about
+// `workgroups` workgroups exist, but never into ranges shorter than `min_range` keys.
+static int auto_splits(const lookat_shape *s, int64_t L, int workgroups = 256, int min_range = 2048)
 {
-    // One range per (b,h) as long as the (b,h) count alone fills the 256 compute units: the
-    // merge kernel is a second launch and costs more than it buys on short contexts.  With
-    // few (b,h) pairs the sequence is cut so that about 512 workgroups exist, but never into
-    // ranges shorter than 1024 keys.
+    // Ungrouped kernels: one workgroup per compute unit and ranges of at least 2048 keys, measured
+    // at d_k = 128, m = 8 (us per call, 2/4/8/16 ranges): 32 (b,h) x 32768 keys: -/55/54/60;
+    // 64 x 32768: 103/95/99/107; 128 x 32768: 183/183/190/-; 32 x 8192: 25.8/18.7/20.4/24.6.
     const int64_t BH = (int64_t)s->B * s->H;
-    int64_t want = 512 / BH;
-    const int64_t cap = (L + 1023) / 1024;
+    int64_t want = workgroups / BH;
+    const int64_t cap = (L + min_range - 1) / min_range;
     if (want > cap)
         want = cap;
     if (want < 1)
@@ -768,6 +771,13 @@ static int auto_splits(const lookat_shape *s, int64_t L)
     if (want > 256)
         want = 256;
     return (int)want;
+}
+// Grouped queries (256-thread workgroups that do `group` times the arithmetic per byte): two
+// workgroups per compute unit up to group 4, one at group 8, measured at 8 x 32 query heads x 32768
+// keys (us per launch, 256 / 512 workgroups): group 4: 131 / 115; group 8: 97 / 110; group 2: 197 / 197.
+static int auto_splits_gqa(const lookat_shape *s, int group, int64_t L)
+{
+    return group <= 4 ? auto_splits(s, L, 512, 1024) : auto_splits(s, L, 256, 1024);
 }
 
 static bool tuned_dk(int d_k) { return d_k == 32 || d_k == 64 || d_k == 128 || d_k == 256; }
@@ -1157,7 +1167,7 @@ extern "C" size_t lookat_attend_decode_gqa_workspace_bytes(const lookat_shape *s
     clear_error();
     if (check_shape(shape) != LOOKAT_OK || L <= 0 || num_splits < 0 || group < 1)
         return 0;
-    const int S = num_splits ? num_splits : auto_splits(shape, L);
+    const int S = num_splits ? num_splits : auto_splits_gqa(shape, group, L);
     if (S == 1)
         return 0;
     return (size_t)shape->B * shape->H * group * S * (shape->d_k + 2) * sizeof(float);
@@ -1206,7 +1216,7 @@ extern "C" int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group
         return fail(LOOKAT_ERR_UNSUPPORTED, "group=%d x m=%d tables (%zu bytes with the reduction buffer) exceed the 160 KB of LDS",
                     group, shape->m, lds);
     const int64_t BH = (int64_t)shape->B * shape->H;   // key/value heads
-    const int S = num_splits ? num_splits : auto_splits(shape, L);
+    const int S = num_splits ? num_splits : auto_splits_gqa(shape, group, L);
     const size_t need = (S == 1) ? 0 : (size_t)BH * group * S * (shape->d_k + 2) * sizeof(float);
     if (need) {
         if (!workspace || workspace_bytes < need)

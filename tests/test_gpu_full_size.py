@@ -95,18 +95,20 @@ def test_config_c1_full_size(lk):
 
 
 def test_config_c3_full_size_long_context(lk):
-    """Llama shape: 32 heads, d_k=128, m=8, batch 8, context 32768 (2.2 GB of codes + values),
-    automatic split count (several ranges per (b,h) merged by the second kernel)."""
+    """Llama shape: 32 heads, d_k=128, m=8, batch 8, context 32768 (2.2 GB of codes + values): the
+    automatic split count (one range: 256 (b,h) pairs fill the chip) and two ranges per (b,h) merged by the
+    second kernel."""
     cfg = li.CONFIGS["C3"]
     case = li.torch_case(li.shrink(cfg, n_calib=2048), "cuda", layer=0)   # calibration set cut: set-up time only
     cb = lk.lookat_kmeans(case["calib"], case["cb_init"], 1)
     scale = 1.0 / math.sqrt(cfg.d_k)
     codes = lk.lookat_encode_keys(case["keys"], cb)
     lut = lk.lookat_build_lut(case["q"], cb)
-    splits = lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L)
-    assert splits > 1
+    assert lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L) == 1
     out = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale)
     assert torch.isfinite(out).all()
+    out2 = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale, num_splits=2)
+    assert float((out2 - out).abs().max()) <= 1e-5
     picks = _sample_bh(cfg, 3, 3)
     cbn = cb.cpu().numpy()
     for b, h in picks:

@@ -772,12 +772,13 @@ static int auto_splits(const lookat_shape *s, int64_t L, int workgroups = 256, i
         want = 256;
     return (int)want;
 }
-// Grouped queries (256-thread workgroups that do `group` times the arithmetic per byte): two
-// workgroups per compute unit up to group 4, one at group 8, measured at 8 x 32 query heads x 32768
-// keys (us per launch, 256 / 512 workgroups): group 4: 131 / 115; group 8: 97 / 110; group 2: 197 / 197.
+// Grouped queries: from group 4 on one 512-thread workgroup per compute unit (see gqa_waves), at
+// group 2 two 256-thread ones.  Measured at 8 x 32 query heads x 32768 keys, d_k = 128, m = 8 (us per
+// launch at 128 / 256 / 512 / 1024 workgroups): group 4: 148 / 102 / 111 / 113; group 8: 127 / 75 / 84 / 102;
+// group 2: 283 / 187 / 186 / 200.
 static int auto_splits_gqa(const lookat_shape *s, int group, int64_t L)
 {
-    return group <= 4 ? auto_splits(s, L, 512, 1024) : auto_splits(s, L, 256, 1024);
+    return group >= 4 ? auto_splits(s, L, 256, 1024) : auto_splits(s, L, 512, 1024);
 }
 
 static bool tuned_dk(int d_k) { return d_k == 32 || d_k == 64 || d_k == 128 || d_k == 256; }
@@ -865,14 +866,28 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
 
 // Grouped queries: 256-thread workgroups; four wavefronts per SIMD up to G = 4 (G accumulator sets
 // per lane fit 128 registers), two for G = 8.
-template <int DK, int G>
+// LDS of a grouped-query workgroup: the group's tables and the per-wavefront partial results.
+static size_t gqa_lds_bytes(int group, int m, int d_k, int waves)
+{
+    return ((size_t)group * m * kCentroids + (size_t)waves * group * (d_k + 2)) * sizeof(float);
+}
+// From group 4 on a workgroup has eight wavefronts where LDS allows: two wavefronts per SIMD share one
+// copy of the group's tables (group x m KB) instead of two four-wavefront workgroups holding a copy
+// each.  B=8, 32 query heads, 32768 keys, d_k=128, m=8: group 8: 81 us against 97 us; group 4: 102
+// against 115 us.
+static int gqa_waves(int group, int m, int d_k)
+{
+    return (group >= 4 && gqa_lds_bytes(group, m, d_k, 2 * kDecWaves) <= 160 * 1024) ? 2 * kDecWaves : kDecWaves;
+}
+
+template <int DK, int G, int GW = kDecWaves>
 static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
-    dim3 block(kDecThreads);
-    const size_t lds = ((size_t)G * a.m * kCentroids + (size_t)kDecWaves * G * (DK + 2)) * sizeof(float);
+    dim3 block(GW * kWave);
+    const size_t lds = gqa_lds_bytes(G, a.m, DK, GW);
 #define LOOKAT_GQA_CASE(M_)                                                                                    \
     case M_: {                                                                                                 \
-        auto kern = decode_split_kernel<DK, M_, kDecWaves, (G <= 4 ? 4 : 3), void, G>;                         \
+        auto kern = decode_split_kernel<DK, M_, GW, (G <= 4 ? 4 : (GW == kDecWaves ? 3 : 2)), void, G>;        \
         if (lds > 64 * 1024) {                                                                                 \
             static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
             if (!configured) {                                                                                 \
@@ -905,9 +920,11 @@ static int launch_gqa_dk(int group, const DecodeArgs &a, dim3 grid, hipStream_t 
     case 2:
         return launch_gqa<DK, 2>(a, grid, st);
     case 4:
-        return launch_gqa<DK, 4>(a, grid, st);
+        return gqa_waves(4, a.m, DK) == kDecWaves ? launch_gqa<DK, 4>(a, grid, st)
+                                                  : launch_gqa<DK, 4, 2 * kDecWaves>(a, grid, st);
     case 8:
-        return launch_gqa<DK, 8>(a, grid, st);
+        return gqa_waves(8, a.m, DK) == kDecWaves ? launch_gqa<DK, 8>(a, grid, st)
+                                                  : launch_gqa<DK, 8, 2 * kDecWaves>(a, grid, st);
     default:
         return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_attend_decode_gqa handles group in {1,2,4,8}; got %d", group);
     }
@@ -1211,7 +1228,7 @@ extern "C" int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group
         return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
     if ((L + 2048) * (int64_t)shape->d_k * 2 > 0xffffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
-    const size_t lds = ((size_t)group * shape->m * kCentroids + (size_t)kDecWaves * group * (shape->d_k + 2)) * sizeof(float);
+    const size_t lds = gqa_lds_bytes(group, shape->m, shape->d_k, gqa_waves(group, shape->m, shape->d_k));
     if (lds > 160 * 1024)
         return fail(LOOKAT_ERR_UNSUPPORTED, "group=%d x m=%d tables (%zu bytes with the reduction buffer) exceed the 160 KB of LDS",
                     group, shape->m, lds);

@@ -318,13 +318,26 @@ def gqa_main(args, cfg, lk, li, torch, device):
         lk.lookat_attend_decode_gqa(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values, scale,
                                     num_splits=splits, workspace=ws, out=ly.out)
 
+    fused = args.path != "calls"
+    for ly in layers:
+        ly.q_step = ly.q[:, :, 0].to(ly.k_step.dtype).contiguous()
+
+    def fused_only(ly):
+        lk.lookat_decode_step_gqa(ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, num_splits=0,
+                                  workspace=ws, out=ly.out)
+
     def step():
         for ly in layers:
-            lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
-            lk.lookat_build_lut(ly.q, ly.cb_q, lut_out=ly.lut)
-            decode_only(ly)
+            if fused:
+                fused_only(ly)
+            else:
+                lk.lookat_encode_keys(ly.new_key, ly.cb, cache=ly.codes, position=cfg.L - 1)
+                lk.lookat_build_lut(ly.q, ly.cb_q, lut_out=ly.lut)
+                decode_only(ly)
 
     step()
+    for ly in layers:   # (the fused step keeps its tables on chip; the checks and the unfused loop below need them)
+        lk.lookat_build_lut(ly.q, ly.cb_q, lut_out=ly.lut)
     torch.cuda.synchronize()
     # the grouped kernel against the plain kernel on caches repeated per query head (layer 0)
     ly = layers[0]
@@ -355,15 +368,20 @@ def gqa_main(args, cfg, lk, li, torch, device):
     elapsed = time.perf_counter() - t0
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     n_launch = max(args.steps, 20) * cfg.layers
-    for ly in layers:
-        decode_only(ly)
-    torch.cuda.synchronize()
-    e0.record()
-    for i in range(n_launch):
-        decode_only(layers[i % cfg.layers])
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / n_launch
+
+    def time_launches(fn):
+        for ly in layers:
+            fn(ly)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n_launch):
+            fn(layers[i % cfg.layers])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n_launch
+
+    us_unfused = time_launches(decode_only)
+    us = time_launches(fused_only) if fused else us_unfused
     kv_bytes = kv.B * kv.H * kv.L * (kv.m + 2 * kv.d_k)
     scores_per_step = cfg.layers * cfg.B * cfg.H * cfg.L
     print(json.dumps({
@@ -374,11 +392,15 @@ def gqa_main(args, cfg, lk, li, torch, device):
         "config": {"workload": f"{cfg.name} with grouped queries: B={cfg.B} query heads={cfg.H} key/value heads={kv.H} "
                                f"(group={g}) L={cfg.L} d_k={cfg.d_k} m={cfg.m} layers={cfg.layers}; per layer "
                                "encode(1 new key) + build_lut + attend_decode_gqa",
+                   "path": "lookat_decode_step_gqa (fused ranges + merge per layer)" if fused
+                           else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode_gqa",
                    "launch": args.mode, "num_splits": "library choice"},
-        "roofline": {"bound": "hbm", "kernel": f"lookat::decode_split_kernel (group of {g} query heads)",
+        "roofline": {"bound": "hbm", "kernel": f"lookat::decode_split_kernel (group of {g} query heads"
+                                               + (", fused step)" if fused else ")"),
                      "achieved": kv_bytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": kv_bytes / us / 1e3 / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": kv_bytes,
                      "us_per_launch": us, "launches_timed": n_launch,
+                     "attend_decode_gqa_alone_us": us_unfused,
                      "query_head_bytes_equivalent_GBs": kv_bytes * g / us / 1e3,
                      "max_abs_diff_vs_ungrouped_kernel": max_diff},
     }), flush=True)

@@ -225,6 +225,35 @@ int lookat_decode_step_split(const lookat_shape *shape, int64_t L,
                              float *out,
                              void *stream);
 
+/*
+ * The fused decode step for grouped-query attention (paper, "Future Work": grouped-query and
+ * multi-query attention; Algorithm 1 per query head, encoding rule of Sec. 3.4 per key/value head):
+ * shape->H counts KEY/VALUE heads, query head hq reads the cache of key/value head hq / group.
+ * For every (b, key/value head): k_new is encoded and appended at row L-1, the tables of the head's
+ * `group` query heads are built from one pass over its codebook and kept on chip, and those query
+ * heads attend over the L cached keys; codes and values are read once per group.  Results equal
+ * lookat_encode_keys + lookat_build_lut (each query head against its key/value head's codebooks)
+ * + lookat_attend_decode_gqa.
+ *   q          [B, H*group, d_k]   k_new  [B, H, d_k]   (both of type qk_dtype, 16-byte aligned)
+ *   codebooks  [H, m, K, d_sub] fp32;  codes, values: the key/value caches as in lookat_decode_step
+ *   out        [B, H*group, d_k] fp32
+ *   num_splits, workspace, workspace_bytes: ranges per (b,h) as in lookat_attend_decode_gqa; the
+ *              workspace size comes from lookat_decode_step_gqa_workspace_bytes
+ * Supported: group in {1, 2, 4, 8}, d_k in {64, 128}, m in {2, 4, 8, 16}, group*m tables plus the
+ * reduction buffer within the 160 KB of LDS; otherwise LOOKAT_ERR_UNSUPPORTED.
+ */
+size_t lookat_decode_step_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L, int32_t num_splits);
+
+int lookat_decode_step_gqa(const lookat_shape *shape, int32_t group, int64_t L,
+                           const void *q, const void *k_new, int qk_dtype,
+                           const float *codebooks,
+                           uint8_t *codes, int64_t code_stride_bh,
+                           const void *values, int64_t value_stride_bh,
+                           float scale, int32_t num_splits,
+                           void *workspace, size_t workspace_bytes,
+                           float *out,
+                           void *stream);
+
 /* The split count lookat_attend_decode uses when num_splits == 0 (host only,
  * no HIP call); 0 if the shape is invalid. */
 int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);

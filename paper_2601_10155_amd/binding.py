@@ -64,6 +64,10 @@ def load_library():
         lib.lookat_decode_step_split_workspace_bytes.restype = sz
         lib.lookat_decode_step_split.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp]
         lib.lookat_decode_step_split.restype = ctypes.c_int
+        lib.lookat_decode_step_gqa_workspace_bytes.argtypes = [sp, i32, i64, i32]
+        lib.lookat_decode_step_gqa_workspace_bytes.restype = sz
+        lib.lookat_decode_step_gqa.argtypes = [sp, i32, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp]
+        lib.lookat_decode_step_gqa.restype = ctypes.c_int
         lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
         lib.lookat_score_prefill.restype = ctypes.c_int
         lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
@@ -284,6 +288,45 @@ def lookat_decode_step_split(q: torch.Tensor, k_new: torch.Tensor, codebooks: to
     """The fused decode step with every (b,h)'s sequence cut into num_splits ranges (0 = the library's
     choice): for few (b,h) pairs and long contexts.  Arguments as lookat_decode_step."""
     return _decode_step(q, k_new, codebooks, codes, values, scale, out, int(num_splits), workspace)
+
+
+def lookat_decode_step_gqa(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
+                           values: torch.Tensor, scale: float, num_splits: int = 0,
+                           workspace: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Fused decode step with grouped queries: q [B,H*g,d_k], k_new [B,H,d_k] (same dtype), codebooks
+    [H,m,256,d_k/m], codes [B,H,L,m] u8 (row L-1 is written), values [B,H,L,d_k] fp16 -> out [B,H*g,d_k] fp32;
+    H counts key/value heads, g = q.shape[1] // H."""
+    lib = load_library()
+    q = _dev(q, "q").contiguous()
+    k_new = _dev(k_new, "k_new").contiguous()
+    cb = _dev(codebooks, "codebooks").contiguous()
+    _dev(codes, "codes"), _dev(values, "values")
+    B, H, L, m = codes.shape
+    d_k = values.shape[3]
+    if q.dim() != 3 or q.shape[0] != B or q.shape[1] % H or q.shape[2] != d_k or q.dtype != k_new.dtype \
+            or k_new.numel() != B * H * d_k:
+        raise ValueError("q must be [B,H*g,d_k] and k_new [B,H,d_k], of one dtype")
+    g = q.shape[1] // H
+    if cb.dtype != torch.float32 or tuple(cb.shape) != (H, m, 256, d_k // m):
+        raise ValueError("codebooks must be fp32 [H,m,256,d_k/m]")
+    if codes.dtype != torch.uint8 or values.dtype != torch.float16 or tuple(values.shape[:3]) != (B, H, L):
+        raise ValueError("codes must be uint8 [B,H,L,m] and values fp16 [B,H,L,d_k]")
+    cs = _bh_stride(codes, "codes")
+    vs = _bh_stride(values, "values")
+    if out is None:
+        out = torch.empty((B, H * g, d_k), dtype=torch.float32, device=values.device)
+    if out.dtype != torch.float32 or out.numel() != B * H * g * d_k or not out.is_contiguous():
+        raise ValueError("out must be contiguous fp32 [B,H*g,d_k]")
+    shape = _Shape(B, H, d_k, m, 256)
+    need = int(lib.lookat_decode_step_gqa_workspace_bytes(ctypes.byref(shape), g, L, num_splits))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=values.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.lookat_decode_step_gqa(ctypes.byref(shape), g, L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
+                                      cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
+                                      int(num_splits), ws_ptr, ws_bytes, out.data_ptr(), _stream(values)))
+    return out
 
 
 def decode_step_split_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, num_splits: int = 0) -> int:

@@ -394,7 +394,9 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // all rows of a group requested together.
 // `encode`: this workgroup's range holds position L-1 (with several ranges per (b,h) only the last one
 // scores the new key and appends its codes; the others build the table alone).
-template <typename FT, int DK, int M>
+// G > 1 (grouped queries): bh is the key/value head; the G query heads bh*G .. bh*G+G-1 each get their
+// table (lut_s[g][i][c]) from the one pass over the key/value head's codebook rows.
+template <typename FT, int DK, int M, int G = 1>
 __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int tid, int lane, int wave, float *lut_s,
                                               double *enc_d, int *enc_c, bool encode)
 {
@@ -403,7 +405,7 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
     float frow[GS][DSUB];
     const float *__restrict__ cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * DSUB + (int64_t)tid * DSUB;
     load_centroid_rows<DSUB, GS>(frow, cbh, 0);
-    const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * DK * sizeof(FT));
+    const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * G * DK * sizeof(FT));
     const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
 #pragma unroll
     for (int i0 = 0; i0 < M; i0 += GS) {
@@ -413,11 +415,14 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
 #pragma unroll
         for (int g = 0; g < GS; ++g) {
             const int i = i0 + g;
-            float e = 0.f;
 #pragma unroll
-            for (int j = 0; j < DSUB; ++j)
-                e = fmaf(uniform_elem<FT>(qg, i * DSUB + j), frow[g][j], e);
-            lut_s[i * kCentroids + tid] = e;
+            for (int hq = 0; hq < G; ++hq) {
+                float e = 0.f;
+#pragma unroll
+                for (int j = 0; j < DSUB; ++j)
+                    e = fmaf(uniform_elem<FT>(qg, hq * DK + i * DSUB + j), frow[g][j], e);
+                lut_s[(hq * M + i) * kCentroids + tid] = e;
+            }
             dv[g] = dm[g] = 0.0;
             if (encode) {
                 dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
@@ -441,7 +446,7 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
 
 // FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused
 // decode step (lookat_decode_step): q and the new key have type FT, the table is computed and
-// the new key encoded by the workgroup itself (WAVES = 4: thread c owns centroid c of every subspace).
+// the new key encoded by the workgroup itself (WAVES = 8; see the roles below).
 // G > 1: grouped-query attention: the workgroup's (b,h) is a KEY/VALUE head shared by G query heads,
 // whose tables (contiguous in memory) are all staged in LDS; codes and values are streamed once.
 // PF: tiles of a wavefront requested before anything else is done (1, or more for the fused step,
@@ -453,7 +458,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
                                       p_L, p_kps, p_scale_log2e, late, !std::is_void<FT>::value);
     constexpr bool FUSED = !std::is_void<FT>::value;
-    static_assert(!FUSED || (WAVES == 2 * kDecWaves && M != 0 && G == 1), "fused step: 512 threads, compile-time m, one query head");
+    static_assert(!FUSED || (WAVES == 2 * kDecWaves && M != 0), "fused step: 512 threads, compile-time m");
     // Fused step: the eight wavefronts take two roles until the table exists.  The first four
     // (256 threads, thread c = centroid c) fetch the codebook rows, build the table and encode the
     // new key (step_prologue) and request no tile before that is done; the other four request
@@ -540,7 +545,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
             // issue ahead of the streamers that share the SIMD: the codebook requests must enter the
             // compute unit's memory queue before the tile requests fill it
             __builtin_amdgcn_s_setprio(3);
-            step_prologue<FT, DK, M>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c, k1 == (uint32_t)a.L);
+            step_prologue<FT, DK, M, G>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c, k1 == (uint32_t)a.L);
             __builtin_amdgcn_s_setprio(0);
         } else {
             LOOKAT_REQUEST_FIRST_TILES()
@@ -913,6 +918,61 @@ static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
 #undef LOOKAT_GQA_CASE
 }
 
+// Fused step with grouped queries: the roles of the ungrouped fused step; the table builders produce the
+// tables of all G query heads from one pass over the key/value head's codebook.  Two workgroups per
+// compute unit at group 2, one from group 4 on (as the unfused grouped kernel).
+static size_t step_gqa_lds_bytes(int group, int m, int d_k)
+{
+    return gqa_lds_bytes(group, m, d_k, kStepWaves) + (size_t)m * kDecWaves * (sizeof(double) + sizeof(int));
+}
+template <int DK, typename FT, int G>
+static int launch_step_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    dim3 block(kStepWaves * kWave);
+    const size_t lds = step_gqa_lds_bytes(G, a.m, DK);
+#define LOOKAT_STEP_GQA_CASE(M_)                                                                               \
+    case M_: {                                                                                                 \
+        auto kern = decode_split_kernel<DK, M_, kStepWaves, ((G == 2 && DK / M_ < 64) ? 4 : 2), FT, G, kStepPrefetch>; \
+        if (lds > 64 * 1024) {                                                                                 \
+            static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
+            if (!configured) {                                                                                 \
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                      \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
+                if (e != hipSuccess)                                                                           \
+                    return fail(LOOKAT_ERR_HIP, "lookat_decode_step_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
+                                hipGetErrorString(e));                                                         \
+                configured = true;                                                                             \
+            }                                                                                                  \
+        }                                                                                                      \
+        hipLaunchKernelGGL(kern, grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));          \
+        return LOOKAT_OK;                                                                                      \
+    }
+    switch (a.m) {
+        LOOKAT_STEP_GQA_CASE(2)
+        LOOKAT_STEP_GQA_CASE(4)
+        LOOKAT_STEP_GQA_CASE(8)
+        LOOKAT_STEP_GQA_CASE(16)
+    default:
+        return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_decode_step_gqa handles m in {2,4,8,16}; got m=%d", a.m);
+    }
+#undef LOOKAT_STEP_GQA_CASE
+}
+
+template <int DK, typename FT>
+static int launch_step_gqa_group(int group, const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    switch (group) {
+    case 2:
+        return launch_step_gqa<DK, FT, 2>(a, grid, st);
+    case 4:
+        return launch_step_gqa<DK, FT, 4>(a, grid, st);
+    case 8:
+        return launch_step_gqa<DK, FT, 8>(a, grid, st);
+    default:
+        return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_decode_step_gqa handles group in {1,2,4,8}; got %d", group);
+    }
+}
+
 template <int DK>
 static int launch_gqa_dk(int group, const DecodeArgs &a, dim3 grid, hipStream_t st)
 {
@@ -934,10 +994,11 @@ static int launch_gqa_dk(int group, const DecodeArgs &a, dim3 grid, hipStream_t 
 
 namespace lookat {
 // Fused step, S ranges per (b,h) (S = 1: no workspace, results written directly).
-static int decode_step_impl(const char *who, const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
-                            int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
-                            const void *values, int64_t value_stride_bh, float scale, int S, void *workspace,
-                            size_t workspace_bytes, float *out, void *stream)
+// group > 1: shape->H counts key/value heads, q and out have group times as many heads.
+static int decode_step_impl(const char *who, const lookat_shape *shape, int group, int64_t L, const void *q,
+                            const void *k_new, int qk_dtype, const float *codebooks, uint8_t *codes,
+                            int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale, int S,
+                            void *workspace, size_t workspace_bytes, float *out, void *stream)
 {
     if (L <= 0)
         return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
@@ -962,8 +1023,11 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int64_t 
         return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: one (b,h) value slab must stay below 4 GiB", (long long)L);
     if (code_stride_bh > 0xffffffffLL || value_stride_bh > 0xffffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "(b,h) strides must stay below 2^32 elements");
+    if (group > 1 && step_gqa_lds_bytes(group, shape->m, shape->d_k) > 160 * 1024)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "group=%d x m=%d tables (%zu bytes with the reduction buffer) exceed the 160 KB of LDS",
+                    group, shape->m, step_gqa_lds_bytes(group, shape->m, shape->d_k));
     const int64_t BH = (int64_t)shape->B * shape->H;
-    const size_t need = (S == 1) ? 0 : (size_t)BH * S * (shape->d_k + 2) * sizeof(float);
+    const size_t need = (S == 1) ? 0 : (size_t)BH * group * S * (shape->d_k + 2) * sizeof(float);
     if (need) {
         if (!workspace || workspace_bytes < need)
             return fail(LOOKAT_ERR_WORKSPACE, "workspace of %zu bytes needed for %d splits, got %zu", need, S,
@@ -998,15 +1062,27 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int64_t 
     a.H = shape->H;
     hipStream_t st = static_cast<hipStream_t>(stream);
     dim3 grid((unsigned)nblocks);
-    bool ok;
-    if (shape->d_k == 64)
-        ok = (qk_dtype == LOOKAT_F16) ? launch_step<64, __half>(a, grid, st) : launch_step<64, float>(a, grid, st);
-    else
-        ok = (qk_dtype == LOOKAT_F16) ? launch_step<128, __half>(a, grid, st) : launch_step<128, float>(a, grid, st);
-    if (!ok)
-        return fail(LOOKAT_ERR_UNSUPPORTED, "no fused kernel for this shape");
+    if (group == 1) {
+        bool ok;
+        if (shape->d_k == 64)
+            ok = (qk_dtype == LOOKAT_F16) ? launch_step<64, __half>(a, grid, st) : launch_step<64, float>(a, grid, st);
+        else
+            ok = (qk_dtype == LOOKAT_F16) ? launch_step<128, __half>(a, grid, st) : launch_step<128, float>(a, grid, st);
+        if (!ok)
+            return fail(LOOKAT_ERR_UNSUPPORTED, "no fused kernel for this shape");
+    } else {
+        int rc;
+        if (shape->d_k == 64)
+            rc = (qk_dtype == LOOKAT_F16) ? launch_step_gqa_group<64, __half>(group, a, grid, st)
+                                          : launch_step_gqa_group<64, float>(group, a, grid, st);
+        else
+            rc = (qk_dtype == LOOKAT_F16) ? launch_step_gqa_group<128, __half>(group, a, grid, st)
+                                          : launch_step_gqa_group<128, float>(group, a, grid, st);
+        if (rc != LOOKAT_OK)
+            return rc;
+    }
     if (S > 1)
-        hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)BH), dim3(kDecThreads), 0, st,
+        hipLaunchKernelGGL(decode_combine_kernel, dim3((unsigned)(BH * group)), dim3(kDecThreads), 0, st,
                            static_cast<const float *>(workspace), out, S, shape->d_k);
     return check_launch(who);
 }
@@ -1020,7 +1096,7 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
     clear_error();
     if (int rc = check_shape(shape))
         return rc;
-    return decode_step_impl("lookat_decode_step", shape, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh, values,
+    return decode_step_impl("lookat_decode_step", shape, 1, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh, values,
                             value_stride_bh, scale, 1, nullptr, 0, out, stream);
 }
 
@@ -1041,8 +1117,34 @@ extern "C" int lookat_decode_step_split(const lookat_shape *shape, int64_t L, co
     if (num_splits < 0 || num_splits > 65535)
         return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
     const int S = num_splits ? num_splits : (L > 0 ? auto_splits(shape, L) : 1);
-    return decode_step_impl("lookat_decode_step_split", shape, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh,
+    return decode_step_impl("lookat_decode_step_split", shape, 1, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh,
                             values, value_stride_bh, scale, S, workspace, workspace_bytes, out, stream);
+}
+
+extern "C" size_t lookat_decode_step_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L,
+                                                         int32_t num_splits)
+{
+    return lookat_attend_decode_gqa_workspace_bytes(shape, group, L, num_splits);
+}
+
+extern "C" int lookat_decode_step_gqa(const lookat_shape *shape, int32_t group, int64_t L, const void *q,
+                                      const void *k_new, int qk_dtype, const float *codebooks, uint8_t *codes,
+                                      int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale,
+                                      int32_t num_splits, void *workspace, size_t workspace_bytes, float *out,
+                                      void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (group != 1 && group != 2 && group != 4 && group != 8)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "lookat_decode_step_gqa handles group in {1,2,4,8}; got %d", group);
+    if (num_splits < 0 || num_splits > 65535)
+        return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
+    const int S = num_splits ? num_splits
+                             : (L > 0 ? (group == 1 ? auto_splits(shape, L) : auto_splits_gqa(shape, group, L)) : 1);
+    return decode_step_impl("lookat_decode_step_gqa", shape, group, L, q, k_new, qk_dtype, codebooks, codes,
+                            code_stride_bh, values, value_stride_bh, scale, S, workspace, workspace_bytes, out, stream);
 }
 
 extern "C" int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L)

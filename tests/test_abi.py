@@ -33,7 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"lookat_encode_keys", "lookat_build_lut", "lookat_attend_decode", "lookat_kmeans_step",
             "lookat_probe_stream_read", "lookat_score_prefill", "lookat_decode_step",
             "lookat_attend_decode_gqa", "lookat_attend_decode_gqa_workspace_bytes", "lookat_decode_step_split",
-            "lookat_decode_step_split_workspace_bytes"} <= set(names)
+            "lookat_decode_step_split_workspace_bytes", "lookat_decode_step_gqa",
+            "lookat_decode_step_gqa_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in lookat.h but not exported"
 
@@ -193,6 +194,34 @@ def test_decode_step_split_argument_errors(lib):
     assert call(wsb=100) == E_WS
     assert call(ws=FAKE + 4) == E_ALIGN
     assert call(out=None) == E_NULL
+
+
+def test_decode_step_gqa_argument_errors(lib):
+    """No call here reaches a launch: every argument list fails a host-side check."""
+    s = Shape(1, 4, 128, 8, 256)      # H = key/value heads
+    f = lib.lookat_decode_step_gqa
+    ws = lib.lookat_decode_step_gqa_workspace_bytes
+    L = 8192
+    assert ws(ctypes.byref(s), 4, L, 1) == 0
+    assert ws(ctypes.byref(s), 4, L, 3) == 1 * 4 * 4 * 3 * (128 + 2) * 4
+    base = [ctypes.byref(s), 4, L, FAKE, FAKE, 1, FAKE, FAKE, L * 8, FAKE, L * 128, ctypes.c_float(0.1), 3, FAKE, 1 << 20,
+            FAKE, None]
+    def call(**kw):
+        a = list(base)
+        for k, v in kw.items():
+            a[{"group": 1, "L": 2, "q": 3, "dt": 5, "splits": 12, "ws": 13, "wsb": 14, "out": 15}[k]] = v
+        return f(*a)
+    assert call(group=3) == E_UNSUP
+    assert call(L=0) == E_SHAPE
+    assert call(dt=0) == E_DTYPE
+    assert call(splits=-2) == E_SHAPE
+    assert call(ws=None) == E_WS
+    assert call(wsb=64) == E_WS
+    assert call(q=None) == E_NULL
+    assert call(out=FAKE + 8) == E_ALIGN
+    big = Shape(1, 4, 128, 16, 256)   # 8 x 16 KB of tables + the reduction buffer do not fit 160 KB of LDS
+    a = list(base); a[0] = ctypes.byref(big); a[1] = 8; a[8] = L * 16
+    assert f(*a) == E_UNSUP
 
 
 def test_attend_decode_gqa_argument_errors(lib):

@@ -503,6 +503,39 @@ def test_decode_step_equals_three_calls(lk):
 
 # ---------------------------------------------------------------- grouped queries ----
 
+@pytest.mark.parametrize("d_k,m", [(128, 8), (64, 4), (64, 16), (128, 2)])
+@pytest.mark.parametrize("g", [2, 4, 8])
+@pytest.mark.parametrize("L,splits", [(1, 0), (65, 0), (1024, 1), (3000, 3), (5000, 0)])
+@pytest.mark.parametrize("qk_dtype", ["float16", "float32"])
+def test_decode_step_gqa_matches_oracle(lk, d_k, m, g, L, splits, qk_dtype):
+    """Fused step with g query heads per key/value head: code cache and every query head's output against
+    the oracle's three steps (encode per key/value head, tables per query head, grouped attention)."""
+    if qk_dtype == "float32" and (g == 8 or L > 1024):
+        pytest.skip("fp32 queries are covered at the smaller shapes")
+    B, H, Lmax = 2, 2, L + 29
+    cfg = li.shrink(li.CONFIGS["C3"], B=B, H=H, L=Lmax, d_k=d_k, m=m, n_calib=400, key_dtype=qk_dtype,
+                    q_dtype=qk_dtype, rank=8 if d_k == 64 else 16)
+    case = li.make_case(cfg, seed=6500 + d_k + m + g + L)
+    cb = case["cb_init"]
+    rng = np.random.default_rng(6600 + d_k + m + g + L)
+    q = (rng.standard_normal((B, H * g, d_k)) / 8).astype(qk_dtype)
+    scale = 1.0 / math.sqrt(d_k)
+    keys, v = case["keys"][:, :, :L], case["values"][:, :, :L]
+    codes_ref = oracle.encode_keys(keys, cb)
+    lut_ref = oracle.build_lut(q[:, :, None], np.repeat(cb, g, axis=0))[:, :, 0]      # [B,H*g,m,256]
+    out_ref = oracle.attend_decode_gqa(lut_ref, codes_ref, v, scale)
+    cache = torch.full((B, H, Lmax, m), 0x5A, dtype=torch.uint8, device="cuda")
+    cache[:, :, :L - 1] = dev(codes_ref[:, :, :L - 1])
+    values = dev(case["values"])
+    out = lk.lookat_decode_step_gqa(dev(q), dev(case["keys"][:, :, L - 1]), dev(cb), cache[:, :, :L], values[:, :, :L],
+                                    scale, num_splits=splits)
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[:, :, :L], codes_ref), "code cache after the step"
+    assert (got[:, :, L:] == 0x5A).all(), "rows past L were touched"
+    assert np.max(np.abs(out.cpu().numpy() - out_ref)) <= OUT_ATOL
+
+
+
 @pytest.mark.parametrize("d_k,m", [(128, 8), (64, 4), (128, 16), (64, 2), (64, 16)])
 @pytest.mark.parametrize("g", [2, 4, 8])
 @pytest.mark.parametrize("L,splits", [(1, 0), (65, 0), (300, 1), (1000, 3), (2500, 0)])

@@ -404,9 +404,20 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
     constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
     float frow[GS][DSUB];
     const float *__restrict__ cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * DSUB + (int64_t)tid * DSUB;
-    load_centroid_rows<DSUB, GS>(frow, cbh, 0);
     const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * G * DK * sizeof(FT));
     const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
+    // The scalar loads of q and k_new are issued a subspace at a time, each shortly before its use, and
+    // the rows are cold (written by the previous layer's kernels): every 128-byte line would cost a
+    // memory round trip in the middle of the table arithmetic.  One word of every line is requested
+    // here, ahead of the codebook rows, so that those loads find the lines in L2.
+    uint32_t touched = 0;
+#pragma unroll
+    for (int o = 0; o < (int)(G * DK * sizeof(FT)); o += 128)
+        touched |= qg[o / 4];
+#pragma unroll
+    for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
+        touched |= kg[o / 4];
+    load_centroid_rows<DSUB, GS>(frow, cbh, 0);
 #pragma unroll
     for (int i0 = 0; i0 < M; i0 += GS) {
         if (i0 > 0)
@@ -423,25 +434,24 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
                     e = fmaf(uniform_elem<FT>(qg, hq * DK + i * DSUB + j), frow[g][j], e);
                 lut_s[(hq * M + i) * kCentroids + tid] = e;
             }
-            dv[g] = dm[g] = 0.0;
-            if (encode) {
-                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
-                dm[g] = dv[g];
-            }
+            // (evaluated in every range, published only where the new key is scored: behind a branch the
+            // scalar loads of k_new would be issued after the table arithmetic, a second memory round
+            // trip in front of the barrier)
+            dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
+            dm[g] = dv[g];
         }
-        if (!encode)
-            continue;
         dmin_wave<GS>(dm);
 #pragma unroll
         for (int g = 0; g < GS; ++g) {
             // lowest lane that holds the wave minimum = lowest centroid index of this wave
             const uint64_t holders = __ballot(dv[g] == dm[g]);
-            if (lane == 0) {
+            if (lane == 0 && encode) {
                 enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
                 enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
             }
         }
     }
+    asm volatile("" ::"s"(touched));   // keeps the early requests alive; nothing reads them
 }
 
 // FT = void: the table comes from memory (lookat_attend_decode).  FT = __half / float: fused

@@ -37,9 +37,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # FETCH_SIZE of lookat::stream_read_kernel in the same run, KiB that kernel reads, WRITE_SIZE
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {
-    ("C1", True): (1247.01, 776.004, 1536.0, 3.375),
+    ("C1", True): (1249.5, 776.004, 1536.0, 3.375),
     ("C1", False): (831.0, 776.004, 1536.0, 3.0),
-    ("C2", True): (26387.6, 24584.0, 49152.0, 108.0),
+    ("C2", True): (26393.1, 24584.0, 49152.0, 108.0),
     ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),

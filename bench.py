@@ -43,7 +43,7 @@ COUNTED_TRAFFIC = {
     ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),
-    ("C4", "score_prefill"): (147935.0, 1.0, 2.0, 2.09826e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
+    ("C4", "score_prefill"): (37045.1, 1.0, 2.0, 2.11e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
 

@@ -5,46 +5,53 @@
 //     scores[b,h,t,l] = sum_i LUT_{b,h,t,i}[codes[b,h,l,i]]   for l <= t + (L - T),  else -inf.
 //
 // Shape of the computation on gfx950
-//   * one workgroup (256 threads = 4 wavefronts) = one (b,h) and kPfGroup consecutive tiles of
-//     TQ = 4 queries; two workgroups fit a compute unit (64 KB of tables each at m = 16), so one
-//     builds tables on the matrix cores while the other gathers from LDS.  Two wavefronts per SIMD
-//     leave each 256 registers: thread c keeps centroid c of EVERY subspace (d_k floats) for all
-//     the workgroup's tiles, so a tile's tables cost no codebook traffic and nothing spills;
-//   * the tables of a tile live in LDS as lut_s[i][c][4] (fp32): the four queries' entries of one
-//     (subspace, centroid) are adjacent, so ONE 16-byte LDS read per (key, subspace) serves four
-//     queries: a quarter of the gather instructions of a [query][i][c] layout;
-//   * table build: per subspace the product [4 queries x d_sub] . [d_sub x 256 centroids] is done
-//     with v_mfma_f32_4x4x1 (16 independent 4x4 outer products per instruction, fp32 in and out).
-//     A = the four queries' coordinate j (lane%4 picks the query, the same in every block),
-//     B = coordinate j of the lane's own centroid, so after d_sub instructions lane c holds the
-//     four queries' entries for centroid c: exactly one 16-byte LDS store.  On the vector ALU the
-//     same build costs 4 FMAs and an LDS operand read per (centroid, coordinate) and was 60% of
-//     the kernel's LDS instructions;
-//   * a thread scores four consecutive keys per step, so its 4 x 4 results leave as one 16-byte
-//     store per query row (1 KB contiguous per wavefront and instruction);
-//   * nothing is loaded from memory inside the tile loop: the workgroup's queries wait in LDS and a
-//     thread's codes (the same keys for every tile) in registers.  Loads and stores share one
-//     in-order counter here, so a wait for a load inside the loop would wait for the tile's 32 KB of
-//     scores to drain as well;
-//   * the scoring loop is bound by LDS gathers (4 bytes per (query, key, subspace)) and by the
-//     scores written to HBM (4 bytes per (query, key), masked ones included).  The gathers hit
-//     random bank groups: an LDS read of 16 bytes per lane is served 8 lanes at a time and 8 random
-//     codes pile 2.7 deep on average (measured 21.8 cycles per gather instruction instead of 8).
-//     A conflict-free variant was built and measured twice: tables as [i/8][c][i%8][4] with lane l
-//     walking the subspaces in the order (u + l) % 8, and the accumulators rotated among registers
-//     before the store so that 8 consecutive lanes store 8 different subspaces (either 8 accumulators
-//     rotated by c%8, or odd 4-lane blocks working on subspaces 4..7,0..3 plus a rotation of 4 by
-//     lane%4).  Both halve the conflict cycles; the first was 30% slower (its selects), the second
-//     exactly as fast as this kernel: the gathers' bank conflicts are not what bounds it.
+//   * queries are taken in tiles of TQ = 4; a tile's tables live in LDS as [i][c][4] (fp32): the
+//     four queries' entries of one (subspace, centroid) are adjacent, so ONE 16-byte LDS read per
+//     (key, subspace) serves four queries;
+//   * one workgroup of 1024 threads per compute unit, two jobs on different wavefronts: wavefronts
+//     0..7 build tables on the matrix cores (and fill the keys no query of a tile may see with
+//     -inf), wavefronts 8..15 score.  The tables are double buffered (2 x 64 KB at m = 16), so tile
+//     n is scored while tile n+1 is built: matrix-core work, vector adds and LDS gathers come from
+//     different wavefronts and overlap.  (With both jobs alternating inside every wavefront, two
+//     256-thread workgroups per compute unit, the phases did not overlap: time = their sum.)
+//   * a workgroup stays on its (b,h) for many tiles (tiles are dealt round-robin to the workgroups
+//     of a (b,h), late ones first, so all workgroups do equal work): the centroid rows and the
+//     codes of the keys a thread scores are the same for every tile and are loaded once.  Nothing
+//     a wavefront waits for is loaded behind its own stores: loads and stores share one in-order
+//     counter, so such a wait would also wait for a tile's scores to drain to HBM.  The queries
+//     of the next tiles are fetched by wavefronts that store nothing.
+//   * table build: per subspace [4 queries x d_sub] . [d_sub x 256 centroids] with
+//     v_mfma_f32_4x4x1 (16 independent 4x4 outer products per instruction, fp32 in and out):
+//     A = the four queries' coordinate (lane%4 picks the query), B = that coordinate of the
+//     lane's own centroid, so after d_sub instructions lane c holds the four queries' entries
+//     for centroid c: one 16-byte LDS store;
+//   * LDS serves its requests in order, and eight scoring wavefronts keep over a hundred gathers
+//     queued: every LDS access of a table builder waits behind them.  So the builders touch LDS
+//     as little as possible: per tile ONE batch of operand reads and the table entries.  Builder
+//     wavefront w owns one half of the subspaces and 64 centroids; a thread keeps its centroid's
+//     d_k/2 coordinates of that half in registers.  The queries sit in LDS permuted so that lane
+//     (block kappa of its 16-lane row, query t) reads the coordinates 4r + kappa of its half with
+//     a few 16-byte reads; the other three coordinates of a group of four come from the
+//     neighbouring blocks of the row by DPP row rotation.  A rotation gives every block a
+//     DIFFERENT coordinate of the group; the 16 blocks of the instruction are independent outer
+//     products, so each thread keeps its centroid's coordinates in the matching rotated order:
+//     every block still accumulates all coordinates of the subspace, in an order that depends on
+//     the block (fp32 sums of d_sub terms: far inside the table tolerance);
+//   * a thread scores four consecutive keys, so its 4 x 4 results leave as one 16-byte store per
+//     query row (1 KB contiguous per wavefront and instruction).  The gathers of a quad run as a
+//     software pipeline of groups of eight: while one group is summed the next is queued in LDS;
+//   * what bounds the kernel at m = 16 is LDS: 4 bytes per (query, key, subspace), gathered from
+//     random bank groups (a 16-byte read per lane is served 8 lanes at a time and 8 random codes
+//     pile 2.7 deep: ~22 cycles per gather instruction instead of 8).  Layouts that make the
+//     gathers conflict-free ([i/8][c][i%8][4] with lane l walking the subspaces in the order
+//     (u + l) % 8) put all lanes of a table STORE on one bank group instead.  At m <= 8 the
+//     bound is the scores written to HBM (4 bytes per (query, key), masked ones included).
 #include "common.h"
 
 namespace lookat {
 
-constexpr int kPfThreads = 256;   // = centroids per subspace: thread c owns centroid c
-constexpr int kPfTQ = 4;      // queries per tile
-constexpr int kPfGroup = 8;   // query tiles per workgroup (codebook registers reused) for 2-byte queries ...
-template <typename QT>
-constexpr int pf_group() { return sizeof(QT) == 2 ? kPfGroup : kPfGroup / 2; }   // ... half as many for fp32: the group's queries wait in LDS
+constexpr int kPfThreads = 256;   // = centroids per subspace
+constexpr int kPfTQ = 4;          // queries per tile
 
 typedef unsigned int pf_v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int pf_v2u __attribute__((ext_vector_type(2)));
@@ -68,7 +75,7 @@ struct PrefillArgs {
     int H;
     int tiles;                // ceil(T / 4)
     int BH;
-    int groups;               // ceil(tiles / tiles per workgroup)
+    int groups;               // workgroups per (b,h)
     int vec4;                 // L % 4 == 0 and scores 16-byte aligned: rows take 16-byte stores
 };
 
@@ -96,245 +103,336 @@ struct PfCodes {
     __device__ __forceinline__ uint32_t byte(int i) const { return (w[i / 4] >> (8 * (i % 4))) & 0xffu; }
 };
 
-// Sum of the four queries' table entries of one key over all subspaces, ascending subspace order
-// (as Algorithm 1 sums), GB gathers requested before the first is used.  Tables as [i][c][4].
-template <int M>
-__device__ __forceinline__ pf_v4f pf_score_key(const float *lut_s, const PfCodes<M> &kc)
+constexpr int kPfBuildThreads = 2 * kPfThreads;               // eight table-building wavefronts
+constexpr int kPfScoreThreads = 2 * kPfThreads;               // eight scoring wavefronts: 2048 keys, one quad per thread
+constexpr int kPfWgThreads = kPfBuildThreads + kPfScoreThreads;
+
+// DPP row_ror:n (rotate right within a 16-lane row): lane l receives the value of lane (l - n) % 16,
+// so rotation 4k brings block kappa the operand of block (kappa - k) % 4.
+template <int N>
+__device__ __forceinline__ float pf_row_from(float x)
 {
-    constexpr int GB = M < 8 ? M : 8;
-    pf_v4f s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i0 = 0; i0 < M; i0 += GB) {
-        pf_v4f v[GB];
-#pragma unroll
-        for (int u = 0; u < GB; ++u)
-            v[u] = *reinterpret_cast<const pf_v4f *>(lut_s + ((i0 + u) * kCentroids + kc.byte(i0 + u)) * kPfTQ);
-#pragma unroll
-        for (int u = 0; u < GB; ++u)
-            s += v[u];
-    }
-    return s;
+    if constexpr (N == 0)
+        return x;
+    else
+        return dpp_mov<0x120 + N>(x, x);
 }
 
-// grid = 8 * ceil(BH / 8) * ceil(tiles / kPfGroup) workgroups, mapped to ((b,h), tile group) below.
+// LDS byte offset of the table of subspace i in buffer b (4 KB each: [256 centroids][4 queries] fp32).
+// The two buffers of a subspace are neighbours, so that one address register per gather serves both
+// with a compile-time offset.
+__host__ __device__ constexpr uint32_t pf_slot(int i, int b) { return (uint32_t)(((i % 8) * 2 + b) * 4096 + (i / 8) * 65536); }
+__host__ __device__ constexpr size_t pf_table_bytes(int m) { return m <= 8 ? (size_t)m * 8192 : 131072; }
+
+// Workgroups per (b,h).  A workgroup fills a compute unit and all workgroups of a launch do the same
+// work, so the launch proceeds in rounds of 256: the smallest count whose last round is at least 95%
+// full (else the fullest), leaving every workgroup eight tiles or more to spread its set-up over.
+static int pf_workgroups(int BH, int tiles)
+{
+    const int jmax = tiles >= 16 ? (tiles / 8 < 64 ? tiles / 8 : 64) : 1;
+    int best = 1;
+    double best_eff = 0.0;
+    for (int j = 1; j <= jmax; ++j) {
+        const double wg = (double)BH * j;
+        const double rounds = (double)((BH * (long long)j + 255) / 256);
+        const double eff = wg / (rounds * 256.0);
+        if (eff > best_eff + 1e-9) {
+            best_eff = eff;
+            best = j;
+        }
+        if (eff >= 0.95)
+            return j;
+    }
+    return best;
+}
+
+typedef const __attribute__((address_space(3))) pf_v4f *PfLdsEntry;
+typedef __attribute__((address_space(3))) pf_v4f *PfLdsStore;
+
+// Scores of four keys against the tile's four queries from table buffer BUF: per key the sum over the
+// subspaces, ascending (as Algorithm 1 sums), of the 16-byte entries [4 queries].  The gathers run as
+// a software pipeline of groups of up to 8: while one group is summed the next is already queued in
+// LDS, so the wavefront always has requests in flight (summing a whole key before requesting the
+// next left LDS idle while the adds ran, and the adds idle while LDS worked: the two times added up).
+template <int M, int BUF>
+__device__ __forceinline__ void pf_score_quad_buf(uint32_t lds_base, const PfCodes<M> (&kq)[4], pf_v4f (&sc)[4])
+{
+    constexpr int GS = M < 8 ? M : 8;   // gathers per group
+    constexpr int GPK = M / GS;         // groups per key
+    constexpr int NG = 4 * GPK;
+    pf_v4f land[2][GS];
+#define LOOKAT_PF_ISSUE(g_)                                                                              \
+    _Pragma("unroll") for (int u = 0; u < GS; ++u)                                                       \
+        land[(g_) & 1][u] = *reinterpret_cast<PfLdsEntry>(                                               \
+            lds_base + kq[(g_) / GPK].byte(((g_) % GPK) * GS + u) * 16u + pf_slot(((g_) % GPK) * GS + u, BUF));
+    LOOKAT_PF_ISSUE(0)
+    LOOKAT_PF_ISSUE(1)
+    __builtin_amdgcn_sched_barrier(0);
+    pf_v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int u = 0; u < GS; ++u)
+            acc = (g % GPK == 0 && u == 0) ? land[g & 1][u] : acc + land[g & 1][u];
+        if (g % GPK == GPK - 1)
+            sc[g / GPK] = acc;
+        if (g + 2 < NG) {
+            LOOKAT_PF_ISSUE(g + 2)
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef LOOKAT_PF_ISSUE
+}
+
 template <typename QT, int DK, int M>
-__global__ __launch_bounds__(kPfThreads, 2) void score_prefill_kernel(const PrefillArgs a)
+__global__ __launch_bounds__(kPfWgThreads, 1) void score_prefill_kernel(const PrefillArgs a)
 {
     constexpr int TQ = kPfTQ;
-    constexpr int NT = kPfThreads;
+    constexpr int NB = kPfBuildThreads;            // table-building threads
+    constexpr int NF = NB / 2;                     // ... of which the first half also fills, the second half fetches queries
+    constexpr int NS = kPfScoreThreads;            // scoring threads
     constexpr int DSUB = DK / M;
-    constexpr int QE = TQ * DK / NT;               // query elements staged per thread and tile
-    constexpr int QS = DK + 4;                     // row stride of q_s in floats
-    constexpr int GROUP = pf_group<QT>();
-    static_assert(NT == kCentroids, "thread c owns centroid c");
-    static_assert(DSUB % 4 == 0 && M % 2 == 0 && (TQ * DK) % NT == 0, "operand reads are 16 bytes wide");
+    constexpr int HALF = DK / 2;                   // coordinates per builder half
+    constexpr int R = HALF / 4;                    // operand values a builder lane holds per tile
+    constexpr int PAIR = (M >= 4) ? 2 : 1;         // subspaces built together
+    constexpr int QSLOT = 2 * TQ * 4 * R;          // floats of one tile's permuted queries (= TQ * DK)
+    constexpr int QE = TQ * DK / NF;               // query elements a fetching thread moves per tile
+    static_assert(DSUB % 4 == 0 && M % 2 == 0 && R % 4 == 0 && (TQ * DK) % NF == 0, "operand reads are 16 bytes wide");
     extern __shared__ __align__(16) float smem[];
-    float *lut_s = smem;                           // [M][256][TQ]
-    float *q_s = smem + M * kCentroids * TQ;       // [2][TQ][QS]: rows 16 bytes apart modulo the 128-byte bank row
-    QT *q_all = reinterpret_cast<QT *>(q_s + 2 * TQ * QS);   // [GROUP][TQ][DK]: the queries of all the workgroup's tiles, as given
-    pf_v4f *lut4 = reinterpret_cast<pf_v4f *>(lut_s);
+    float *q_p = smem + pf_table_bytes(M) / sizeof(float);   // [2 slots][2 halves][TQ][4 blocks][R] fp32, permuted
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)smem;
 
-    // Workgroup ids are dealt round-robin to the 8 dies, each with its own 4 MB L2.  (b,h) pairs
-    // are assigned so that a die only ever sees the heads congruent to its index mod 8: its L2
-    // then holds a few heads' codebooks (128 KB each at d_k = 128) instead of cycling through all
-    // of them.  Within a die, late (long) tile groups come first.
+    // a.groups workgroups per (b,h); workgroup j of them takes the tiles tiles-1-j, tiles-1-j-groups, ...
+    // (late tiles see more keys: dealing them round-robin gives every workgroup the same work).
+    // Workgroup ids go round-robin to the 8 dies; a die only sees the heads congruent to its index.
     const int xcd = blockIdx.x % 8;
     const int slot = blockIdx.x / 8;
     const int bh_per_xcd = (a.BH + 7) / 8;
     const int bh = (slot % bh_per_xcd) * 8 + xcd;
-    const int group = a.groups - 1 - slot / bh_per_xcd;
-    if (bh >= a.BH)
+    const int j_wg = slot / bh_per_xcd;
+    if (bh >= a.BH || a.tiles - 1 - j_wg < 0)
         return;
     const int h = bh % a.H;
-    const int tid = threadIdx.x;
-    const int64_t off = a.L - a.T;            // query t sits at position t + off
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    const bool builds = wave < NB / kWave;
+    const int tid = builds ? (int)threadIdx.x : (int)threadIdx.x - NB;   // index within the role
+    const int64_t off = a.L - a.T;
     const QT *qg = static_cast<const QT *>(a.q) + (int64_t)bh * a.T * DK;
     const uint8_t *codes_bh = a.codes + (int64_t)bh * a.code_stride;
     float *scores_bh = a.scores + (int64_t)bh * a.T * a.L;
-    // centroid `tid` of every subspace, kept for all tiles of the workgroup
-    float row[M][DSUB];
-#pragma unroll
-    for (int i = 0; i < M; ++i) {
-        const float4 *src =
-            reinterpret_cast<const float4 *>(a.codebooks + (((int64_t)h * M + i) * kCentroids + tid) * DSUB);
-#pragma unroll
-        for (int j4 = 0; j4 < DSUB / 4; ++j4) {
-            const float4 v = src[j4];
-            row[i][4 * j4] = v.x;
-            row[i][4 * j4 + 1] = v.y;
-            row[i][4 * j4 + 2] = v.z;
-            row[i][4 * j4 + 3] = v.w;
-        }
-    }
+    const int tile_first = a.tiles - 1 - j_wg;
+    const int stride = a.groups;
+    const int n = tile_first / stride + 1;        // tiles of this workgroup: tile_first - k*stride, k = 0 .. n-1
+    // Step s = 0 .. n: tile k = s is built into table buffer s % 2 while tile k = s-1 is scored from the
+    // other one; one workgroup barrier per step (both roles run the same count).
 
-    // Everything the tiles need from memory is requested here, before the first score is stored:
-    // loads and stores share one in-order counter on this chip, and a wait for a load that is mixed
-    // with stores waits for ALL of them, i.e. for a tile's 32 KB of scores to drain to HBM.  Inside
-    // the tile loop there are then stores only.
-    //   * the queries of all GROUP tiles go to LDS as they are (converted tile by tile later);
-    //   * the codes a thread scores are the same for every tile (keys 4*tid .. 4*tid+3 and the
-    //     same 1024 further on): two such quads stay in registers (contexts up to 2048 keys; beyond
-    //     that a loop with loads takes over).  Always issued, at an index clamped into the cache:
-    //     plain values, no partly written arrays.
-    const int tile_lo = group * GROUP;
-    const int tile_hi = (tile_lo + GROUP - 1 < a.tiles) ? tile_lo + GROUP - 1 : a.tiles - 1;
-    for (int x = tid; x < GROUP * TQ * DK; x += NT) {
-        const int t = tile_lo * TQ + x / DK;
-        q_all[x] = (t < a.T) ? qg[(int64_t)t * DK + x % DK] : QT(0.f);
-    }
-    const int last_key = (int)(a.L - 1);
-    PfCodes<M> ka0, ka1, ka2, ka3, kb0, kb1, kb2, kb3;
-#define LOOKAT_PF_LOAD_QUAD(k0_, k1_, k2_, k3_, l0_)                                         \
-    do {                                                                                     \
-        const int q0_ = (l0_);                                                               \
-        k0_.load(codes_bh + (int64_t)(q0_ < last_key ? q0_ : last_key) * M);                 \
-        k1_.load(codes_bh + (int64_t)(q0_ + 1 < last_key ? q0_ + 1 : last_key) * M);         \
-        k2_.load(codes_bh + (int64_t)(q0_ + 2 < last_key ? q0_ + 2 : last_key) * M);         \
-        k3_.load(codes_bh + (int64_t)(q0_ + 3 < last_key ? q0_ + 3 : last_key) * M);         \
-    } while (0)
-    LOOKAT_PF_LOAD_QUAD(ka0, ka1, ka2, ka3, 4 * tid);
-    LOOKAT_PF_LOAD_QUAD(kb0, kb1, kb2, kb3, 4 * tid + 4 * NT);
-#define LOOKAT_PF_KEEP(k_)                                   \
-    _Pragma("unroll") for (int w_ = 0; w_ < (M + 3) / 4; ++w_) asm volatile("" : "+v"(k_.w[w_]))
-    // (a first "use" of the cached codes here, so that the wait for their loads sits in front of
-    // the tile loop and not, re-executed with stores in flight, inside it)
-    LOOKAT_PF_KEEP(ka0);
-    LOOKAT_PF_KEEP(ka1);
-    LOOKAT_PF_KEEP(ka2);
-    LOOKAT_PF_KEEP(ka3);
-    LOOKAT_PF_KEEP(kb0);
-    LOOKAT_PF_KEEP(kb1);
-    LOOKAT_PF_KEEP(kb2);
-    LOOKAT_PF_KEEP(kb3);
-    __syncthreads();   // q_all complete
-    auto stage_q = [&](int tile, float *dst) {   // a tile's queries: LDS as given -> LDS fp32, padded rows
+    if (builds) {
+        const int half = (wave / 2) & 1;                 // subspaces half*M/2 .. +M/2-1 (wavefronts 0,1,4,5 / 2,3,6,7)
+        const bool fetches = wave >= NF / kWave;         // wavefronts 4..7 move the queries, 0..3 fill
+        const int c = (wave & 1) * 64 + ((wave >> 2) & 1) * 128 + (tid & 63);   // the thread's centroid
+        const int kappa = (tid >> 2) & 3;                // its 4-lane block within the 16-lane row
+        const int ft = tid & (NF - 1);                   // index among the filling / fetching threads
+        // the centroid's coordinates of this half; register 4r+k holds coordinate 4r + (kappa - k) % 4,
+        // the one that rotation 4k brings to this block
+        float row[HALF];
 #pragma unroll
-        for (int e = 0; e < QE; ++e) {
-            const int x = tid + e * NT;
-            dst[(x / DK) * QS + x % DK] = pf_to_f32<QT>(q_all[(tile - tile_lo) * (TQ * DK) + x]);
-        }
-    };
-    stage_q(tile_hi, q_s);
-    int cur = 0;
-
-    for (int tile = tile_hi; tile >= tile_lo; --tile) {
-        const int t0 = tile * TQ;
-        const int64_t vis_last = t0 + TQ - 1 + off;                     // last key any query of the tile sees
-        const int kmax = (int)((vis_last + 1 < a.L) ? vis_last + 1 : a.L);
-        const float *q_lane = q_s + cur * (TQ * QS) + (tid & 3) * QS;   // matrix operand: query (lane % 4) of the tile
-
-        __syncthreads();   // this tile's queries are staged; the previous tile's readers are done with lut_s
-
-        // ---- tables as [i][c][4]: lut4[i*256 + c] = (q[t]^(i) . C_i[c])_{t=0..3}, j ascending ----
-        // Two subspaces at a time: their accumulator chains are independent, so one chain's
-        // matrix-core latency is covered by the other's instruction.
-#pragma unroll
-        for (int i = 0; i < M; i += 2) {
-            pf_v4f acc0 = {0.f, 0.f, 0.f, 0.f};
-            pf_v4f acc1 = {0.f, 0.f, 0.f, 0.f};
+        for (int il = 0; il < M / 2; ++il) {
+            const float *src = a.codebooks + (((int64_t)h * M + half * (M / 2) + il) * kCentroids + c) * DSUB;
 #pragma unroll
             for (int j4 = 0; j4 < DSUB / 4; ++j4) {
-                const pf_v4f x0 = *reinterpret_cast<const pf_v4f *>(q_lane + i * DSUB + 4 * j4);
-                const pf_v4f x1 = *reinterpret_cast<const pf_v4f *>(q_lane + (i + 1) * DSUB + 4 * j4);
+                const float4 v = *reinterpret_cast<const float4 *>(src + 4 * j4);
+                const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    acc0 = __builtin_amdgcn_mfma_f32_4x4x1f32(x0[u], row[i][4 * j4 + u], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_4x4x1f32(x1[u], row[i + 1][4 * j4 + u], acc1, 0, 0, 0);
+                for (int k = 0; k < 4; ++k) {
+                    const int w = (kappa - k) & 3;
+                    row[il * DSUB + 4 * j4 + k] = (w == 0) ? e[0] : (w == 1) ? e[1] : (w == 2) ? e[2] : e[3];
                 }
             }
-            lut4[i * kCentroids + tid] = acc0;
-            lut4[(i + 1) * kCentroids + tid] = acc1;
         }
-        if (tile > tile_lo)
-            stage_q(tile - 1, q_s + (cur ^ 1) * (TQ * QS));
-        cur ^= 1;
+        // A tile's queries travel global memory -> registers of the fetching wavefronts (one step
+        // ahead) -> LDS, permuted: q_p[slot][half][t][kappa][r] = q[tile, query t][half*HALF + 4r + kappa]
+        // (one more step ahead) -> operand registers of all builders (one more step).  The fetching
+        // wavefronts issue no stores, so waiting for their loads does not wait for anybody's scores.
+        QT qf[QE], qf0[QE], qf1[QE];
+#define LOOKAT_PF_FETCH_Q(k_, dst_)                                                                      \
+    _Pragma("unroll") for (int e = 0; e < QE; ++e)                                                       \
+    {                                                                                                    \
+        const int x_ = ft + e * NF;                                                                      \
+        const int64_t t_ = (int64_t)(tile_first - (k_) * stride) * TQ + x_ / DK;                         \
+        dst_[e] = ((k_) < n && t_ < a.T) ? qg[t_ * DK + x_ % DK] : QT(0.f);                              \
+    }
+#define LOOKAT_PF_PUT_Q(slot_, src_)                                                                     \
+    _Pragma("unroll") for (int e = 0; e < QE; ++e)                                                       \
+    {                                                                                                    \
+        const int x_ = ft + e * NF;                                                                      \
+        const int tq_ = x_ / DK, jh_ = (x_ % DK) / HALF, jl_ = (x_ % DK) % HALF;                         \
+        q_p[(slot_) * QSLOT + ((jh_ * TQ + tq_) * 4 + (jl_ & 3)) * R + (jl_ >> 2)] = pf_to_f32<QT>(src_[e]); \
+    }
+        const float *q_lane = q_p + ((half * TQ + (tid & 3)) * 4 + kappa) * R;
+        pf_v4f qv[R / 4];
+#define LOOKAT_PF_LOAD_OPERAND(slot_)                                                                    \
+    _Pragma("unroll") for (int r4 = 0; r4 < R / 4; ++r4)                                                 \
+        qv[r4] = *reinterpret_cast<const pf_v4f *>(q_lane + (slot_) * QSLOT + 4 * r4);
+        if (fetches) {
+            LOOKAT_PF_FETCH_Q(0, qf0)
+            LOOKAT_PF_FETCH_Q(1, qf1)
+            LOOKAT_PF_FETCH_Q(2, qf)
+            LOOKAT_PF_PUT_Q(0, qf0)
+            LOOKAT_PF_PUT_Q(1, qf1)
+        }
+        uint32_t st_lo = lds_base + (uint32_t)c * 16u;   // table entries of centroid c: two bases, a ds_write offset spans 64 KB
+        uint32_t st_hi = st_lo + 65536u;
+        asm volatile("" : "+v"(st_lo), "+v"(st_hi));
+        __syncthreads();   // the first two tiles' queries are in LDS
+        LOOKAT_PF_LOAD_OPERAND(0)
         __syncthreads();
-
-        // ---- scoring: four consecutive keys per thread and step, four scores per key ----
-        // A thread's 4 keys x 4 queries come out as four 16-byte pieces, one per query row, so a
-        // wavefront writes 1 KB of contiguous scores per store instruction (with one key per lane
-        // it would be 256 bytes, and the kernel's 2 GB of output four times the store instructions).
-        float *rowp[TQ];   // score rows of the tile: uniform bases (scalar registers)
-#pragma unroll
-        for (int t = 0; t < TQ; ++t)
-            rowp[t] = scores_bh + (int64_t)(t0 + t) * a.L;
-        auto score_quad = [&](int l0, const PfCodes<M> &k0, const PfCodes<M> &k1, const PfCodes<M> &k2,
-                              const PfCodes<M> &k3) {
-            pf_v4f sc[4];
-            sc[0] = pf_score_key<M>(lut_s, k0);
-            sc[1] = pf_score_key<M>(lut_s, k1);
-            __builtin_amdgcn_sched_barrier(0);   // two keys' gathers in flight at a time: more would only fill registers
-            sc[2] = pf_score_key<M>(lut_s, k2);
-            sc[3] = pf_score_key<M>(lut_s, k3);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t = 0; t < TQ; ++t) {
-                const int tq = t0 + t;
-                if (tq >= a.T)
-                    continue;
-                pf_v4f o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    o[j] = (l0 + j <= tq + off) ? sc[j][t] : -INFINITY;   // keys of the quad past the tile's range are masked too
-                if (a.vec4) {
-                    *reinterpret_cast<pf_v4f *>(rowp[t] + (uint32_t)l0) = o;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (l0 + j < a.L)
-                            rowp[t][(uint32_t)(l0 + j)] = o[j];
-                }
-            }
-        };
-        // The gather addresses depend only on the cached codes, so the compiler would compute all
-        // of them (8 keys x m subspaces) once, outside the tile loop, and spill them.  Declaring the
-        // cached code words modified here keeps that arithmetic (a byte extract and a shift-add per
-        // gather) inside the loop.
-        LOOKAT_PF_KEEP(ka0);
-        LOOKAT_PF_KEEP(ka1);
-        LOOKAT_PF_KEEP(ka2);
-        LOOKAT_PF_KEEP(ka3);
-        LOOKAT_PF_KEEP(kb0);
-        LOOKAT_PF_KEEP(kb1);
-        LOOKAT_PF_KEEP(kb2);
-        LOOKAT_PF_KEEP(kb3);
-#undef LOOKAT_PF_KEEP
-        if (4 * tid < kmax)
-            score_quad(4 * tid, ka0, ka1, ka2, ka3);
-        if (4 * tid + 4 * NT < kmax)
-            score_quad(4 * tid + 4 * NT, kb0, kb1, kb2, kb3);
-        for (int l0 = 4 * tid + 8 * NT; l0 < kmax; l0 += 4 * NT) {   // contexts beyond the cached quads
-            PfCodes<M> kc0, kc1, kc2, kc3;
-            LOOKAT_PF_LOAD_QUAD(kc0, kc1, kc2, kc3, l0);
-            score_quad(l0, kc0, kc1, kc2, kc3);
+#define LOOKAT_PF_BUILD_STEP(BUF_, s_)                                                                   \
+    if ((s_) < n) {                                                                                      \
+        const int tile_ = tile_first - (s_) * stride;                                                    \
+        /* PAIR subspaces at a time: their accumulator chains are independent, so one chain's */        \
+        /* matrix-core latency is covered by the other's instruction */                                  \
+        _Pragma("unroll") for (int il = 0; il < M / 2; il += PAIR)                                       \
+        {                                                                                                \
+            pf_v4f acc[PAIR];                                                                            \
+            _Pragma("unroll") for (int p = 0; p < PAIR; ++p) acc[p] = pf_v4f{0.f, 0.f, 0.f, 0.f};        \
+            _Pragma("unroll") for (int j4 = 0; j4 < DSUB / 4; ++j4)                                      \
+            {                                                                                            \
+                float x[PAIR];                                                                           \
+                _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                         \
+                    x[p] = qv[(((il + p) * DSUB) / 4 + j4) / 4][(((il + p) * DSUB) / 4 + j4) % 4];       \
+                _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                         \
+                    acc[p] = __builtin_amdgcn_mfma_f32_4x4x1f32(pf_row_from<0>(x[p]), row[(il + p) * DSUB + 4 * j4 + 0], acc[p], 0, 0, 0);  \
+                _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                         \
+                    acc[p] = __builtin_amdgcn_mfma_f32_4x4x1f32(pf_row_from<4>(x[p]), row[(il + p) * DSUB + 4 * j4 + 1], acc[p], 0, 0, 0);  \
+                _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                         \
+                    acc[p] = __builtin_amdgcn_mfma_f32_4x4x1f32(pf_row_from<8>(x[p]), row[(il + p) * DSUB + 4 * j4 + 2], acc[p], 0, 0, 0);  \
+                _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                         \
+                    acc[p] = __builtin_amdgcn_mfma_f32_4x4x1f32(pf_row_from<12>(x[p]), row[(il + p) * DSUB + 4 * j4 + 3], acc[p], 0, 0, 0); \
+            }                                                                                            \
+            _Pragma("unroll") for (int p = 0; p < PAIR; ++p)                                             \
+            {                                                                                            \
+                if (half == 0)                                                                           \
+                    *reinterpret_cast<PfLdsStore>((il + p < 8 ? st_lo : st_hi) + (pf_slot(il + p, BUF_) & 0xffffu)) = acc[p];                  \
+                else                                                                                     \
+                    *reinterpret_cast<PfLdsStore>((M / 2 + il + p < 8 ? st_lo : st_hi) + (pf_slot(M / 2 + il + p, BUF_) & 0xffffu)) = acc[p];  \
+            }                                                                                            \
+        }                                                                                                \
+        if (fetches) {                                                                                   \
+            /* tile s+2 (fetched during the last step) to the LDS slot tile s has left; tile s+3 requested */ \
+            LOOKAT_PF_PUT_Q(BUF_, qf)                                                                    \
+            LOOKAT_PF_FETCH_Q((s_) + 3, qf)                                                              \
+        } else {                                                                                         \
+            /* keys no query of the tile may see */                                                      \
+            const int t0_ = tile_ * TQ;                                                                  \
+            const int64_t vis_ = t0_ + TQ - 1 + off;                                                     \
+            const int64_t kmax_ = (vis_ + 1 < a.L) ? vis_ + 1 : a.L;                                     \
+            const int64_t kfill_ = (kmax_ + 3) / 4 * 4;                                                  \
+            for (int t = 0; t < TQ && t0_ + t < a.T; ++t) {                                              \
+                float *rowp_ = scores_bh + (int64_t)(t0_ + t) * a.L;                                     \
+                if (a.vec4) {                                                                            \
+                    const pf_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};                    \
+                    for (uint32_t l = (uint32_t)kfill_ + 4 * ft; l < (uint32_t)a.L; l += 4 * NF)         \
+                        *reinterpret_cast<pf_v4f *>(rowp_ + l) = ninf;                                   \
+                } else {                                                                                 \
+                    for (uint32_t l = (uint32_t)kfill_ + ft; l < (uint32_t)a.L; l += NF)                 \
+                        rowp_[l] = -INFINITY;                                                            \
+                }                                                                                        \
+            }                                                                                            \
+        }                                                                                                \
+        LOOKAT_PF_LOAD_OPERAND((BUF_) ^ 1)   /* tile s+1, in LDS since the last step */                  \
+    }
+        for (int s = 0; s <= n; s += 2) {
+            LOOKAT_PF_BUILD_STEP(0, s)
+            __syncthreads();
+            LOOKAT_PF_BUILD_STEP(1, s + 1)
+            __syncthreads();
         }
-        // ---- keys no query of the tile may see (from the end of the last quad on) ----
-        const int64_t kfill = ((int64_t)kmax + 3) / 4 * 4;
-        for (int t = 0; t < TQ; ++t) {
-            const int tq = t0 + t;
-            if (tq >= a.T)
-                break;
-            if (a.vec4) {
-                const pf_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                for (int64_t l = kfill + 4 * tid; l < a.L; l += 4 * NT)
-                    *reinterpret_cast<pf_v4f *>(rowp[t] + l) = ninf;
-            } else {
-                for (int64_t l = kfill + tid; l < a.L; l += NT)
-                    rowp[t][l] = -INFINITY;
-            }
+#undef LOOKAT_PF_BUILD_STEP
+#undef LOOKAT_PF_LOAD_OPERAND
+#undef LOOKAT_PF_PUT_Q
+#undef LOOKAT_PF_FETCH_Q
+    } else {
+        // A thread scores the same four consecutive keys (4*tid ..) in every tile, so their codes stay in
+        // registers (contexts up to 2048 keys; beyond that a loop with loads takes over).
+        const int last_key = (int)(a.L - 1);
+        const int l_own = 4 * tid;
+        PfCodes<M> kq[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            kq[k].load(codes_bh + (int64_t)(l_own + k < last_key ? l_own + k : last_key) * M);
+#define LOOKAT_PF_KEEP_CODES(k_)                                                                         \
+    _Pragma("unroll") for (int w_ = 0; w_ < (M + 3) / 4; ++w_) asm volatile("" : "+v"(k_.w[w_]));
+        LOOKAT_PF_KEEP_CODES(kq[0])
+        LOOKAT_PF_KEEP_CODES(kq[1])
+        LOOKAT_PF_KEEP_CODES(kq[2])
+        LOOKAT_PF_KEEP_CODES(kq[3])
+        __syncthreads();
+        __syncthreads();
+#define LOOKAT_PF_STORE_QUAD(l0_, sc_)                                                                   \
+    _Pragma("unroll") for (int t = 0; t < TQ; ++t)                                                       \
+    {                                                                                                    \
+        const int tq_ = t0_ + t;                                                                         \
+        if (tq_ < a.T) {                                                                                 \
+            float *rowp_ = scores_bh + (int64_t)tq_ * a.L;                                               \
+            pf_v4f o_;                                                                                   \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
+                o_[j] = ((l0_) + j <= tq_ + off) ? sc_[j][t] : -INFINITY;                                \
+            if (a.vec4) {                                                                                \
+                *reinterpret_cast<pf_v4f *>(rowp_ + (uint32_t)(l0_)) = o_;                               \
+            } else {                                                                                     \
+                _Pragma("unroll") for (int j = 0; j < 4; ++j)                                            \
+                    if ((l0_) + j < a.L)                                                                 \
+                        rowp_[(uint32_t)((l0_) + j)] = o_[j];                                            \
+            }                                                                                            \
+        }                                                                                                \
+    }
+#define LOOKAT_PF_SCORE_QUAD(BUF_, l0_, kq_)                                                             \
+    {                                                                                                    \
+        pf_v4f sc_[4];                                                                                   \
+        pf_score_quad_buf<M, BUF_>(lds_base, kq_, sc_);                                                  \
+        LOOKAT_PF_STORE_QUAD(l0_, sc_)                                                                   \
+    }
+#define LOOKAT_PF_SCORE_STEP(BUF_, s_)                                                                   \
+    if ((s_) >= 1 && (s_) <= n) {                                                                        \
+        const int t0_ = (tile_first - ((s_) - 1) * stride) * TQ;                                         \
+        const int64_t vis_ = t0_ + TQ - 1 + off;                                                         \
+        const int kmax_ = (int)((vis_ + 1 < a.L) ? vis_ + 1 : a.L);                                      \
+        /* the address arithmetic of the cached codes stays here, inside the loop: hoisted out, the */   \
+        /* addresses of all (key, subspace) pairs would want 64 more registers */                        \
+        LOOKAT_PF_KEEP_CODES(kq[0])                                                                      \
+        LOOKAT_PF_KEEP_CODES(kq[1])                                                                      \
+        LOOKAT_PF_KEEP_CODES(kq[2])                                                                      \
+        LOOKAT_PF_KEEP_CODES(kq[3])                                                                      \
+        if (l_own < kmax_)                                                                               \
+            LOOKAT_PF_SCORE_QUAD(BUF_, l_own, kq)                                                        \
+        for (int l0 = l_own + 4 * NS; l0 < kmax_; l0 += 4 * NS) {                                        \
+            PfCodes<M> kc_[4];                                                                           \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
+                kc_[j].load(codes_bh + (int64_t)(l0 + j < last_key ? l0 + j : last_key) * M);            \
+            LOOKAT_PF_SCORE_QUAD(BUF_, l0, kc_)                                                          \
+        }                                                                                                \
+    }
+        for (int s = 0; s <= n; s += 2) {
+            LOOKAT_PF_SCORE_STEP(1, s)        // tile s-1 sits in buffer (s-1) % 2 = 1
+            __syncthreads();
+            LOOKAT_PF_SCORE_STEP(0, s + 1)
+            __syncthreads();
         }
+#undef LOOKAT_PF_SCORE_STEP
+#undef LOOKAT_PF_SCORE_QUAD
+#undef LOOKAT_PF_STORE_QUAD
+#undef LOOKAT_PF_KEEP_CODES
     }
 }
-
-#undef LOOKAT_PF_LOAD_QUAD
 
 template <typename QT, int DK, int M>
 static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
 {
     PrefillArgs a = a0;
     a.tiles = (a.T + kPfTQ - 1) / kPfTQ;
-    const size_t lds = ((size_t)M * kCentroids * kPfTQ + 2 * (size_t)kPfTQ * (DK + 4)) * sizeof(float) +
-                       (size_t)pf_group<QT>() * kPfTQ * DK * sizeof(QT);
+    a.BH = BH;
+    a.groups = pf_workgroups(BH, a.tiles);
+    const size_t lds = pf_table_bytes(M) + 2 * (size_t)kPfTQ * DK * sizeof(float);   // two table buffers, two tiles of queries
     auto kern = score_prefill_kernel<QT, DK, M>;
     if (lds > 64 * 1024) {
         static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS
@@ -347,10 +445,8 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
             configured = true;
         }
     }
-    a.BH = BH;
-    a.groups = (a.tiles + pf_group<QT>() - 1) / pf_group<QT>();
     dim3 grid((unsigned)((BH + 7) / 8 * 8 * a.groups));
-    hipLaunchKernelGGL(kern, grid, dim3(kPfThreads), lds, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(kPfWgThreads), lds, st, a);
     return check_launch("lookat_score_prefill");
 }
 
@@ -390,6 +486,8 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
         return fail(LOOKAT_ERR_DTYPE, "q_dtype=%d is neither LOOKAT_F16 nor LOOKAT_F32", q_dtype);
     if (!q || !codebooks || !codes || !scores)
         return fail(LOOKAT_ERR_NULL, "q, codebooks, codes and scores must be non-NULL");
+    if (L > (1LL << 30))
+        return fail(LOOKAT_ERR_UNSUPPORTED, "L=%lld: a row of scores is addressed with 32-bit byte offsets (L <= 2^30)", (long long)L);
     if (code_stride_bh < L * shape->m)
         return fail(LOOKAT_ERR_SHAPE, "code_stride_bh=%lld is smaller than L*m", (long long)code_stride_bh);
     if (!aligned16(q) || !aligned16(codebooks) || (reinterpret_cast<uintptr_t>(scores) & 3u))
@@ -397,12 +495,8 @@ extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_
     const int cvec = (shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16) ? shape->m : 1;
     if ((reinterpret_cast<uintptr_t>(codes) % cvec) || (code_stride_bh % cvec))
         return fail(LOOKAT_ERR_ALIGN, "codes and code_stride_bh must be multiples of %d bytes for m=%d", cvec, shape->m);
-    {
-        const int64_t BHp = ((int64_t)shape->B * shape->H + 7) / 8 * 8;
-        const int64_t groups = ((int64_t)(T + kPfTQ - 1) / kPfTQ + kPfGroup / 2 - 1) / (kPfGroup / 2);   // the smaller group size
-        if (BHp * groups > 0x7fffffffLL)
-            return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*T=%lld*%d exceeds one launch", (long long)shape->B * shape->H, T);
-    }
+    if (((int64_t)shape->B * shape->H + 7) / 8 * 8 * 64 > 0x7fffffffLL)   // at most 64 workgroups per (b,h)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "B*H=%lld exceeds one launch", (long long)shape->B * shape->H);
     PrefillArgs a;
     a.q = q;
     a.codebooks = codebooks;

@@ -392,10 +392,12 @@ def _prefill_check(lk, case, cb, codes):
 
 @pytest.mark.parametrize("d_k,m", [(128, 16), (128, 8), (64, 4), (64, 2), (64, 16)])
 @pytest.mark.parametrize("q_dtype", ["float16", "float32"])
-@pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135), (64, 0), (40, 24), (300, 1300)])
+@pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135), (64, 0), (40, 24), (300, 1300),
+                                     (40, 2101), (100, 4200)])
 def test_score_prefill_parity(lk, d_k, m, q_dtype, T, extra):
-    """Ragged query tiles (T not a multiple of 8 or 32), queries that are the tail of a longer
-    cache (extra > 0), a single query, a block whose late tiles take several 256-key steps."""
+    """Ragged query tiles (T not a multiple of 4), one workgroup per (b,h) and several, queries that are
+    the tail of a longer cache (extra > 0), a single query, contexts beyond the 2048 keys whose codes
+    the scoring threads keep in registers (one and two further rounds of keys, L odd: scalar stores)."""
     L = T + extra
     cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)
     case = li.make_case(cfg, seed=5000 + d_k + m + T)

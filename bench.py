@@ -43,7 +43,7 @@ COUNTED_TRAFFIC = {
     ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),
-    ("C4", "score_prefill"): (37045.1, 1.0, 2.0, 2.11e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
+    ("C4", "score_prefill"): (37033.6, 1.0, 2.0, 2.10989e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
 
@@ -477,7 +477,7 @@ def prefill_main(args, cfg, lk, li, torch, device):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} T=L={cfg.L} d_k={cfg.d_k} m={cfg.m} K={cfg.K}; "
                                "encode_keys (fp16 keys) + build_lut (T queries per head, materialised) + score_prefill"},
-        "roofline": {"bound": "alu", "kernel": "lookat::score_prefill_kernel (LDS gather bound)",
+        "roofline": {"bound": "alu", "kernel": "lookat::score_prefill_kernel (priced against LDS gather bytes)",
                      "achieved": lds_bytes / us["score_prefill"] / 1e3, "peak": LDS_PEAK, "unit": "GB/s",
                      "frac": lds_bytes / us["score_prefill"] / 1e3 / LDS_PEAK,
                      "traffic": counted_traffic((cfg.name, "score_prefill")),

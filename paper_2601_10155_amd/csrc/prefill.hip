@@ -40,12 +40,15 @@
 //   * a thread scores four consecutive keys, so its 4 x 4 results leave as one 16-byte store per
 //     query row (1 KB contiguous per wavefront and instruction).  The gathers of a quad run as a
 //     software pipeline of groups of eight: while one group is summed the next is queued in LDS;
-//   * what bounds the kernel at m = 16 is LDS: 4 bytes per (query, key, subspace), gathered from
-//     random bank groups (a 16-byte read per lane is served 8 lanes at a time and 8 random codes
-//     pile 2.7 deep: ~22 cycles per gather instruction instead of 8).  Layouts that make the
-//     gathers conflict-free ([i/8][c][i%8][4] with lane l walking the subspaces in the order
-//     (u + l) % 8) put all lanes of a table STORE on one bank group instead.  At m <= 8 the
-//     bound is the scores written to HBM (4 bytes per (query, key), masked ones included).
+//   * at m = 16 the gathers (4 bytes per (query, key, subspace)) hit random bank groups — the
+//     table of a subspace is [256 centroids][16 bytes] — and cost about twice a conflict-free
+//     read.  A layout without conflicts (one 128-byte row per centroid holding 8 subspaces, lane
+//     l gathering column (u + l) % 8, the builders rotating their entries among registers by
+//     lane so that their stores spread over the columns too) was built and ran exactly as fast:
+//     LDS throughput is not what bounds the kernel; vector-instruction issue (6 instructions per
+//     gather, the builders' matrix and DPP instructions), dependency latency inside a wavefront
+//     and the wait for the slowest wavefront at every step are.  At m <= 8 the bound is the
+//     scores written to HBM (4 bytes per (query, key), masked ones included).
 #include "common.h"
 
 namespace lookat {
@@ -114,8 +117,8 @@ __device__ __forceinline__ float pf_row_from(float x)
 {
     if constexpr (N == 0)
         return x;
-    else
-        return dpp_mov<0x120 + N>(x, x);
+    else   // every lane is written, so there is no previous value to keep (and no copy to make first)
+        return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), 0x120 + N, 0xf, 0xf, false));
 }
 
 // LDS byte offset of the table of subspace i in buffer b (4 KB each: [256 centroids][4 queries] fp32).
@@ -376,7 +379,7 @@ __global__ __launch_bounds__(kPfWgThreads, 1) void score_prefill_kernel(const Pr
             float *rowp_ = scores_bh + (int64_t)tq_ * a.L;                                               \
             pf_v4f o_;                                                                                   \
             _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
-                o_[j] = ((l0_) + j <= tq_ + off) ? sc_[j][t] : -INFINITY;                                \
+                o_[j] = ((l0_) + j <= tq_ + (int)off) ? sc_[j][t] : -INFINITY;                           \
             if (a.vec4) {                                                                                \
                 *reinterpret_cast<pf_v4f *>(rowp_ + (uint32_t)(l0_)) = o_;                               \
             } else {                                                                                     \

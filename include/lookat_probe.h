@@ -28,7 +28,7 @@ int lookat_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, void
 
 /*
  * Writes `bytes` bytes starting at `dst` (device pointer, 16-byte aligned, bytes a multiple of
- * 16) once, with 16-byte stores of the 32-bit pattern `word`, 32 bytes per thread: the write-stream
+ * 16) once, with 16-byte stores of the 32-bit pattern `word`, one per thread: the write-stream
  * counterpart, for the kernels whose cost is their output (the materialised tables of
  * lookat_build_lut with many queries, the score block of lookat_score_prefill).  Asynchronous on
  * `stream`.  Returns 0, or a negative lookat_status from lookat.h.

@@ -505,15 +505,18 @@ def test_decode_step_equals_three_calls(lk):
 
 # ---------------------------------------------------------------- grouped queries ----
 
+# fp16 queries and keys over the whole grid; fp32 at the smaller groups and contexts
+_STEP_GQA_CASES = [(dt, g, L, splits)
+                   for dt in ("float16", "float32") for g in (2, 4, 8)
+                   for (L, splits) in ((1, 0), (65, 0), (1024, 1), (3000, 3), (5000, 0))
+                   if dt == "float16" or (g < 8 and L <= 1024)]
+
+
 @pytest.mark.parametrize("d_k,m", [(128, 8), (64, 4), (64, 16), (128, 2)])
-@pytest.mark.parametrize("g", [2, 4, 8])
-@pytest.mark.parametrize("L,splits", [(1, 0), (65, 0), (1024, 1), (3000, 3), (5000, 0)])
-@pytest.mark.parametrize("qk_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("qk_dtype,g,L,splits", _STEP_GQA_CASES)
 def test_decode_step_gqa_matches_oracle(lk, d_k, m, g, L, splits, qk_dtype):
     """Fused step with g query heads per key/value head: code cache and every query head's output against
     the oracle's three steps (encode per key/value head, tables per query head, grouped attention)."""
-    if qk_dtype == "float32" and (g == 8 or L > 1024):
-        pytest.skip("fp32 queries are covered at the smaller shapes")
     B, H, Lmax = 2, 2, L + 29
     cfg = li.shrink(li.CONFIGS["C3"], B=B, H=H, L=Lmax, d_k=d_k, m=m, n_calib=400, key_dtype=qk_dtype,
                     q_dtype=qk_dtype, rank=8 if d_k == 64 else 16)

@@ -410,13 +410,16 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
     // the rows are cold (written by the previous layer's kernels): every 128-byte line would cost a
     // memory round trip in the middle of the table arithmetic.  One word of every line is requested
     // here, ahead of the codebook rows, so that those loads find the lines in L2.
+    // (Ungrouped only: with grouped queries, whose workgroups stream megabytes each, it measured slower.)
     uint32_t touched = 0;
+    if constexpr (G == 1) {
 #pragma unroll
-    for (int o = 0; o < (int)(G * DK * sizeof(FT)); o += 128)
-        touched |= qg[o / 4];
+        for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
+            touched |= qg[o / 4];
 #pragma unroll
-    for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
-        touched |= kg[o / 4];
+        for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
+            touched |= kg[o / 4];
+    }
     load_centroid_rows<DSUB, GS>(frow, cbh, 0);
 #pragma unroll
     for (int i0 = 0; i0 < M; i0 += GS) {
@@ -434,20 +437,24 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
                     e = fmaf(uniform_elem<FT>(qg, hq * DK + i * DSUB + j), frow[g][j], e);
                 lut_s[(hq * M + i) * kCentroids + tid] = e;
             }
-            // (evaluated in every range, published only where the new key is scored: behind a branch the
-            // scalar loads of k_new would be issued after the table arithmetic, a second memory round
-            // trip in front of the barrier)
-            dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
-            dm[g] = dv[g];
+            if (G == 1 || encode) {
+                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
+                dm[g] = dv[g];
+            }
         }
-        dmin_wave<GS>(dm);
+        // Ungrouped, the distances are evaluated in every range and published only where the new key is
+        // scored: the branch would cost more than the arithmetic.  With grouped queries the ranges that
+        // do not hold the new key skip them (eight heads' tables already keep those wavefronts busy).
+        if (G == 1 || encode) {
+            dmin_wave<GS>(dm);
 #pragma unroll
-        for (int g = 0; g < GS; ++g) {
-            // lowest lane that holds the wave minimum = lowest centroid index of this wave
-            const uint64_t holders = __ballot(dv[g] == dm[g]);
-            if (lane == 0 && encode) {
-                enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
-                enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+            for (int g = 0; g < GS; ++g) {
+                // lowest lane that holds the wave minimum = lowest centroid index of this wave
+                const uint64_t holders = __ballot(dv[g] == dm[g]);
+                if (lane == 0 && encode) {
+                    enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
+                    enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+                }
             }
         }
     }

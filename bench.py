@@ -6,7 +6,9 @@ encode the new token's key into the code cache, build the query's lookup tables,
 the coded cache.  `--path fused` (the default where the shape has a fused instance) does the
 three in ONE kernel per layer (lookat_decode_step); `--path calls` makes the three library
 calls (lookat_encode_keys, lookat_build_lut, lookat_attend_decode).  The step is captured in a
-HIP graph (`--mode graph`, default) and every replay is compared with the eager result.
+HIP graph and every replay is compared with the eager result; `--mode auto` (default) then times a
+few untimed steps both ways, replayed from the graph and as plain C-ABI calls, and runs the warm-up
+and the timed steps the faster way (`config.launch` says which; `--mode graph|eager` force one).
 Inputs are seeded and synthetic (lookat_inputs), resident in HBM before the timed region;
 codebooks come from the library's own Lloyd iterations on seeded calibration keys.
 `--workload C4` times the prefill block instead (encode, table build, causal scoring).
@@ -54,6 +56,30 @@ def counted_traffic(key):
     return int(round((fetch * known_kib / stream_fetch + write_kib) * 1024.0))
 
 
+def pick_launch_mode(mode, step, replay, trial_steps=10):
+    """The way the steps are launched: `step` (plain C-ABI calls) or `replay` (the captured graph).
+    With mode "auto", both run `trial_steps` untimed-region steps and the faster is taken (a graph
+    node costs the GPU about half a microsecond more than a queued launch; plain calls cost host time
+    per launch, which only matters when a step has many short kernels)."""
+    import torch
+    if mode == "eager" or replay is None:
+        return step, "eager"
+    if mode == "graph":
+        return replay, "graph"
+    took = {}
+    for name, fn in (("graph", replay), ("eager", step)):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(trial_steps):
+            fn()
+        torch.cuda.synchronize()
+        took[name] = (time.perf_counter() - t0) / trial_steps
+    name = "graph" if took["graph"] <= took["eager"] else "eager"
+    other = "eager" if name == "graph" else "graph"
+    return (replay if name == "graph" else step), f"{name} (auto; {other}: {took[other] * 1e3:.4f} ms/step in the trial)"
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,8 +87,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"],
                     help="C1..C3: decode step (C2 is the configuration the metric is quoted on); C4: prefill block")
-    ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
-                    help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time")
+    ap.add_argument("--mode", default="auto", choices=["auto", "graph", "eager"],
+                    help="graph: one step captured in a HIP graph and replayed; eager: one C-ABI call at a time; "
+                         "auto: whichever of the two runs a few untimed steps faster")
     ap.add_argument("--path", default="auto", choices=["auto", "fused", "calls"],
                     help="fused: one lookat_decode_step per layer; calls: encode_keys + build_lut + attend_decode; "
                          "auto: fused wherever the library has a fused kernel for the shape")
@@ -173,9 +200,8 @@ def main():
     torch.cuda.synchronize()
     eager_out = [ly.out.clone() for ly in layers]
 
-    run_step = step
     graph = None
-    if args.mode == "graph":
+    if args.mode != "eager":
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -185,7 +211,6 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        run_step = graph.replay
         for _ in range(2):              # replays must reproduce the eager step exactly
             for ly in layers:
                 ly.out.zero_()
@@ -194,6 +219,8 @@ def main():
             for ly, ref in zip(layers, eager_out):
                 if not torch.equal(ly.out, ref):
                     raise RuntimeError("graph replay differs from the eager step")
+
+    run_step, launch = pick_launch_mode(args.mode, step, graph.replay if graph is not None else None)
 
     # ---- timed region: W warm-up steps, then exactly K steps ----------------------------
     for _ in range(args.warmup):
@@ -263,7 +290,7 @@ def main():
             "path": ("lookat_decode_step_split (fused ranges + merge per layer)" if fused_split
                      else "lookat_decode_step (one fused kernel per layer)") if fused
                     else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode",
-            "values": "fp16", "codes": "u8 (" + args.codes + ")", "lut": "f32", "launch": args.mode, "num_splits": splits,
+            "values": "fp16", "codes": "u8 (" + args.codes + ")", "lut": "f32", "launch": launch, "num_splits": splits,
             "codebooks": f"{args.kmeans_iters} Lloyd iterations (lookat_kmeans_step) on {cfg.n_calib} seeded "
                          "calibration keys per head",
         },
@@ -346,8 +373,8 @@ def gqa_main(args, cfg, lk, li, torch, device):
                                   ly.values.repeat_interleave(g, dim=1).contiguous(), scale)
     max_diff = float((ref - ly.out).abs().max())
     del ref
-    run_step = step
-    if args.mode == "graph":
+    graph = None
+    if args.mode != "eager":
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -357,7 +384,7 @@ def gqa_main(args, cfg, lk, li, torch, device):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        run_step = graph.replay
+    run_step, launch = pick_launch_mode(args.mode, step, graph.replay if graph is not None else None)
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
@@ -394,7 +421,7 @@ def gqa_main(args, cfg, lk, li, torch, device):
                                "encode(1 new key) + build_lut + attend_decode_gqa",
                    "path": "lookat_decode_step_gqa (fused ranges + merge per layer)" if fused
                            else "lookat_encode_keys + lookat_build_lut + lookat_attend_decode_gqa",
-                   "launch": args.mode, "num_splits": "library choice"},
+                   "launch": launch, "num_splits": "library choice"},
         "roofline": {"bound": "hbm", "kernel": f"lookat::decode_split_kernel (group of {g} query heads"
                                                + (", fused step)" if fused else ")"),
                      "achieved": kv_bytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",

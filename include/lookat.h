@@ -264,15 +264,17 @@ int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);
  * with its T x T attention maps).  The T queries are the last T positions of the cache:
  * query t sits at position t + (L - T) and sees the keys l <= t + (L - T).
  *     scores[b,h,t,l] = sum_i ( sum_j q[b,h,t, i*d_sub + j] * codebooks[h,i, codes[b,h,l,i], j] )
- * for visible l (table entries accumulated in fp32 in ascending j, then summed in ascending
- * i), and -inf elsewhere.  The per-query tables stay on chip; nothing but `scores` is written.
+ * for visible l (table entries accumulated in fp32, the coordinates j in ascending groups of
+ * four whose inner order depends on the centroid; entries then summed in ascending i), and
+ * -inf elsewhere.  The per-query tables stay on chip; nothing but `scores` is written.
  *
  *   q          [B,H,T,d_k] q_dtype (fp16 or fp32), 16-byte aligned, dense
  *   codebooks  [H,m,K,d_sub] fp32, 16-byte aligned
  *   codes      element (b,h,l,i) at codes[(b*H+h)*code_stride_bh + l*m + i], alignment as in
  *              lookat_attend_decode
  *   scores     out [B,H,T,L] fp32 (unscaled), 4-byte aligned
- * Supported shapes: d_k in {64, 128}, m in {2, 4, 8, 16}; others: LOOKAT_ERR_UNSUPPORTED.
+ * Supported shapes: d_k in {64, 128}, m in {2, 4, 8, 16}, L <= 2^30; others:
+ * LOOKAT_ERR_UNSUPPORTED.
  */
 int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_t L,
                          const void *q, int q_dtype,

@@ -145,6 +145,7 @@ def test_score_prefill_argument_errors(lib):
     assert call(cs=64 * 16 - 16) == E_SHAPE
     assert call(q=FAKE + 2) == E_ALIGN
     assert call(codes=FAKE + 8) == E_ALIGN
+    assert call(L=(1 << 30) + 64, cs=((1 << 30) + 64) * 16) == E_UNSUP    # rows of scores beyond 32-bit byte offsets
     bad = Shape(2, 3, 96, 4, 256)
     a = list(ok_args); a[0] = ctypes.byref(bad); a[7] = 64 * 4
     assert f(*a) == E_UNSUP

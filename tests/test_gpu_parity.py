@@ -406,6 +406,30 @@ def test_score_prefill_parity(lk, d_k, m, q_dtype, T, extra):
     _prefill_check(lk, case, cb, codes)
 
 
+def test_score_prefill_single_head_and_padded_cache(lk):
+    """One (b,h) with many tiles (its tiles are dealt to many workgroups) and codes that are the front
+    part of a longer cache (slab stride larger than L*m)."""
+    T, L, Lmax = 600, 700, 1000
+    cfg = li.shrink(li.CONFIGS["C4"], B=1, H=1, L=Lmax, T=T, d_k=128, m=16, n_calib=400)
+    case = li.make_case(cfg, seed=5077)
+    cb = case["cb_init"]
+    codes_all = oracle.encode_keys(case["keys"], cb)                 # [1,1,Lmax,m]
+    codes = codes_all[:, :, :L]
+    q = case["q"]
+    ref = oracle.score_prefill(oracle.build_lut(q, cb), np.ascontiguousarray(codes))
+    cache = dev(codes_all)
+    got = lk.lookat_score_prefill(dev(q), dev(cb), cache[:, :, :L]).cpu().numpy()
+    vis = np.isfinite(ref)
+    assert np.array_equal(np.isneginf(got), ~vis), "mask differs"
+    d_sub = cb.shape[3]
+    qa = np.abs(q.astype(np.float64)).reshape(1, 1, T, 16, d_sub)
+    picked = np.stack([np.abs(cb.astype(np.float64))[0, i, codes[0, 0, :, i].astype(np.int64)] for i in range(16)],
+                      axis=1)[None, None]                                            # [1,1,L,m,d_sub]
+    mag = np.einsum("bhtid,bhlid->bhtl", qa, picked)
+    err = np.abs(got[vis].astype(np.float64) - ref[vis].astype(np.float64))
+    assert np.all(err <= REL * np.maximum(mag[vis], 1e-6)), f"max err {err.max()}"
+
+
 def test_score_prefill_matches_decode_rows(lk):
     """Row t of the causal block equals the decode scores of query t over the first t+1 keys."""
     cfg = li.shrink(li.CONFIGS["C4"], B=1, H=2, L=200, T=200, n_calib=400)

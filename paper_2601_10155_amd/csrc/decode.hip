@@ -209,9 +209,14 @@ __device__ __forceinline__ void load_rows(v4u (&v)[CH], __amdgpu_buffer_rsrc_t r
 {
     // lane (rowin, sub) reads 16 bytes at row*DK*2 + sub*16 = (row0*DK*2) + lane*16: 1 KB per load
     constexpr uint32_t kGroupBytes = kWave * 16;
+    // Non-temporal (aux bit 1): the rows are read once and should not displace tables, codebooks and
+    // queries from the caches; measured 11.94 -> 11.29 us per fused launch at batch 32 x 12 heads x 1024
+    // keys (the same hint on the code loads as well: 11.39).
+    constexpr int kStreamOnce = 2;
 #pragma unroll
     for (int j = 0; j < CH; ++j)
-        v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, kb * (DK * 2) + (g0 + j) * kGroupBytes + lane * 16, 0, 0);
+        v[j] = __builtin_amdgcn_raw_buffer_load_b128(rv, kb * (DK * 2) + (g0 + j) * kGroupBytes + lane * 16, 0,
+                                                     kStreamOnce);
 }
 
 // ---- pieces of the fused decode step ---------------------------------------------------

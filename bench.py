@@ -40,9 +40,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {
     ("C1", True): (1249.5, 776.004, 1536.0, 3.375),
-    ("C1", False): (831.0, 776.004, 1536.0, 3.0),
-    ("C2", True): (26393.1, 24584.0, 49152.0, 108.0),
-    ("C2", False): (26151.0, 24584.0, 49152.0, 96.0),
+    ("C1", False): (826.5, 776.004, 1536.0, 3.0),
+    ("C2", True): (26393.0, 24584.0, 49152.0, 108.0),
+    ("C2", False): (26144.5, 24584.0, 49152.0, 96.0),
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),
     ("C4", "score_prefill"): (37033.6, 1.0, 2.0, 2.10989e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)

@@ -81,7 +81,7 @@ typedef struct {
  *   N          keys per (b,h), >= 0 (N == 0 is a no-op that returns LOOKAT_OK)
  */
 int lookat_encode_keys(const lookat_shape *shape, int64_t N,
-                       const void *keys, int key_dtype,
+                       const void *keys, lookat_dtype key_dtype,
                        const float *codebooks,
                        uint8_t *codes, int64_t code_stride_bh,
                        void *stream);
@@ -98,7 +98,7 @@ int lookat_encode_keys(const lookat_shape *shape, int64_t N,
  *   T          queries per (b,h), >= 1 (decode: T = 1)
  */
 int lookat_build_lut(const lookat_shape *shape, int32_t T,
-                     const void *q, int q_dtype,
+                     const void *q, lookat_dtype q_dtype,
                      const float *codebooks,
                      float *lut,
                      void *stream);
@@ -192,7 +192,7 @@ int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group, int64_t L
  * Supported shapes: d_k in {64, 128}, m in {2, 4, 8, 16}; others: LOOKAT_ERR_UNSUPPORTED.
  */
 int lookat_decode_step(const lookat_shape *shape, int64_t L,
-                       const void *q, const void *k_new, int qk_dtype,
+                       const void *q, const void *k_new, lookat_dtype qk_dtype,
                        const float *codebooks,
                        uint8_t *codes, int64_t code_stride_bh,
                        const void *values, int64_t value_stride_bh,
@@ -216,7 +216,7 @@ int lookat_decode_step(const lookat_shape *shape, int64_t L,
 size_t lookat_decode_step_split_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits);
 
 int lookat_decode_step_split(const lookat_shape *shape, int64_t L,
-                             const void *q, const void *k_new, int qk_dtype,
+                             const void *q, const void *k_new, lookat_dtype qk_dtype,
                              const float *codebooks,
                              uint8_t *codes, int64_t code_stride_bh,
                              const void *values, int64_t value_stride_bh,
@@ -245,7 +245,7 @@ int lookat_decode_step_split(const lookat_shape *shape, int64_t L,
 size_t lookat_decode_step_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L, int32_t num_splits);
 
 int lookat_decode_step_gqa(const lookat_shape *shape, int32_t group, int64_t L,
-                           const void *q, const void *k_new, int qk_dtype,
+                           const void *q, const void *k_new, lookat_dtype qk_dtype,
                            const float *codebooks,
                            uint8_t *codes, int64_t code_stride_bh,
                            const void *values, int64_t value_stride_bh,
@@ -257,6 +257,15 @@ int lookat_decode_step_gqa(const lookat_shape *shape, int32_t group, int64_t L,
 /* The split count lookat_attend_decode uses when num_splits == 0 (host only,
  * no HIP call); 0 if the shape is invalid. */
 int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);
+
+/* The launch shape lookat_attend_decode takes for this problem (host only, no HIP call):
+ * *ranges = ranges per (b,h) (num_splits, or the library's choice when it is 0), *wavefronts =
+ * wavefronts per workgroup of the kernel instance that streams a range (4 for ranges under
+ * 2048 keys and for shapes without a large-workgroup instance, 16 otherwise).  Either pointer
+ * may be NULL.  Exists so that tests can state which instance a shape exercises.  Returns a
+ * lookat_status. */
+int lookat_attend_decode_launch_shape(const lookat_shape *shape, int64_t L, int32_t num_splits,
+                                      int32_t *ranges, int32_t *wavefronts);
 
 /*
  * Causal lookup-and-sum scoring of a block of T queries against L >= T coded keys
@@ -277,7 +286,7 @@ int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, int64_t L);
  * LOOKAT_ERR_UNSUPPORTED.
  */
 int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_t L,
-                         const void *q, int q_dtype,
+                         const void *q, lookat_dtype q_dtype,
                          const float *codebooks,
                          const uint8_t *codes, int64_t code_stride_bh,
                          float *scores,

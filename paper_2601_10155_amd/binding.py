@@ -52,6 +52,8 @@ def load_library():
         lib.lookat_attend_decode_workspace_bytes.restype = sz
         lib.lookat_attend_decode_auto_splits.argtypes = [sp, i64]
         lib.lookat_attend_decode_auto_splits.restype = i32
+        lib.lookat_attend_decode_launch_shape.argtypes = [sp, i64, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.lookat_attend_decode_launch_shape.restype = ctypes.c_int
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
         lib.lookat_attend_decode_gqa_workspace_bytes.argtypes = [sp, i32, i64, i32]
@@ -204,6 +206,15 @@ def attend_decode_gqa_workspace_bytes(B: int, H: int, group: int, d_k: int, m: i
 def attend_decode_auto_splits(B: int, H: int, d_k: int, m: int, L: int) -> int:
     shape = _Shape(B, H, d_k, m, 256)
     return int(load_library().lookat_attend_decode_auto_splits(ctypes.byref(shape), L))
+
+
+def attend_decode_launch_shape(B: int, H: int, d_k: int, m: int, L: int, num_splits: int = 0) -> tuple[int, int]:
+    """(ranges per (b,h), wavefronts per workgroup) of the launch lookat_attend_decode makes for this problem."""
+    shape = _Shape(B, H, d_k, m, 256)
+    ranges, waves = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load_library().lookat_attend_decode_launch_shape(ctypes.byref(shape), L, num_splits, ctypes.byref(ranges),
+                                                            ctypes.byref(waves)))
+    return int(ranges.value), int(waves.value)
 
 
 def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,

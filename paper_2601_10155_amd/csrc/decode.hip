@@ -12,7 +12,6 @@
 //     (online softmax), so the streaming loop has no workgroup barrier;
 //   * the sequence is cut into `splits` ranges per (b,h) (flash-decoding style); the
 //     ranges are merged by a second small kernel.
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -843,14 +842,8 @@ static void launch_tuned(const DecodeArgs &a, dim3 grid, hipStream_t st)
 // MI355X: the small workgroup wins at context 1024, the large one from 16K keys on).
 static int pick_waves(int d_k, int m, int64_t keys_per_split)
 {
-    static const int forced = [] {
-        const char *e = getenv("LOOKAT_DECODE_WAVES");
-        return e ? atoi(e) : 0;
-    }();
     if ((d_k != 64 && d_k != 128) || (m != 2 && m != 4 && m != 8))
         return 4;   // the 16-wave variant must fit 64 registers; only these shapes do
-    if (forced == 4 || forced == 16 || (forced == 8 && d_k == 64))
-        return forced;
     return keys_per_split >= 32 * kTile ? 16 : 4;
 }
 
@@ -916,15 +909,12 @@ static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
     case M_: {                                                                                                 \
         auto kern = decode_split_kernel<DK, M_, GW, (G <= 4 ? 4 : (GW == kDecWaves ? 3 : 2)), void, G>;        \
         if (lds > 64 * 1024) {                                                                                 \
-            static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
-            if (!configured) {                                                                                 \
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                      \
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
-                if (e != hipSuccess)                                                                           \
-                    return fail(LOOKAT_ERR_HIP, "lookat_attend_decode_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
-                                hipGetErrorString(e));                                                         \
-                configured = true;                                                                             \
-            }                                                                                                  \
+            /* allow more than 64 KB of dynamic LDS: idempotent, so every call makes it (no shared flag) */   \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                          \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
+            if (e != hipSuccess)                                                                               \
+                return fail(LOOKAT_ERR_HIP, "lookat_attend_decode_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
+                            hipGetErrorString(e));                                                             \
         }                                                                                                      \
         hipLaunchKernelGGL(kern, grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, false), late_of(a));         \
         return LOOKAT_OK;                                                                                      \
@@ -956,15 +946,12 @@ static int launch_step_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
     case M_: {                                                                                                 \
         auto kern = decode_split_kernel<DK, M_, kStepWaves, ((G == 2 && DK / M_ < 64) ? 4 : 2), FT, G, kStepPrefetch>; \
         if (lds > 64 * 1024) {                                                                                 \
-            static bool configured = false; /* per instantiation: allow more than 64 KB of dynamic LDS */     \
-            if (!configured) {                                                                                 \
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                      \
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);     \
-                if (e != hipSuccess)                                                                           \
-                    return fail(LOOKAT_ERR_HIP, "lookat_decode_step_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
-                                hipGetErrorString(e));                                                         \
-                configured = true;                                                                             \
-            }                                                                                                  \
+            /* allow more than 64 KB of dynamic LDS: idempotent, so every call makes it (no shared flag) */   \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                          \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);         \
+            if (e != hipSuccess)                                                                               \
+                return fail(LOOKAT_ERR_HIP, "lookat_decode_step_gqa: cannot reserve %zu bytes of LDS: %s", lds, \
+                            hipGetErrorString(e));                                                             \
         }                                                                                                      \
         hipLaunchKernelGGL(kern, grid, block, lds, st, LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));          \
         return LOOKAT_OK;                                                                                      \
@@ -1111,7 +1098,7 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
 }  // namespace lookat
 
 extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
-                                  int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                  lookat_dtype qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
                                   const void *values, int64_t value_stride_bh, float scale, float *out, void *stream)
 {
     using namespace lookat;
@@ -1128,7 +1115,7 @@ extern "C" size_t lookat_decode_step_split_workspace_bytes(const lookat_shape *s
 }
 
 extern "C" int lookat_decode_step_split(const lookat_shape *shape, int64_t L, const void *q, const void *k_new,
-                                        int qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                        lookat_dtype qk_dtype, const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
                                         const void *values, int64_t value_stride_bh, float scale, int32_t num_splits,
                                         void *workspace, size_t workspace_bytes, float *out, void *stream)
 {
@@ -1150,7 +1137,7 @@ extern "C" size_t lookat_decode_step_gqa_workspace_bytes(const lookat_shape *sha
 }
 
 extern "C" int lookat_decode_step_gqa(const lookat_shape *shape, int32_t group, int64_t L, const void *q,
-                                      const void *k_new, int qk_dtype, const float *codebooks, uint8_t *codes,
+                                      const void *k_new, lookat_dtype qk_dtype, const float *codebooks, uint8_t *codes,
                                       int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale,
                                       int32_t num_splits, void *workspace, size_t workspace_bytes, float *out,
                                       void *stream)
@@ -1178,6 +1165,25 @@ extern "C" int32_t lookat_attend_decode_auto_splits(const lookat_shape *shape, i
     return auto_splits(shape, L);
 }
 
+extern "C" int lookat_attend_decode_launch_shape(const lookat_shape *shape, int64_t L, int32_t num_splits,
+                                                 int32_t *ranges, int32_t *wavefronts)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (L <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
+    if (num_splits < 0 || num_splits > 65535)
+        return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
+    const int S = num_splits ? num_splits : auto_splits(shape, L);
+    if (ranges)
+        *ranges = S;
+    if (wavefronts)
+        *wavefronts = tuned_dk(shape->d_k) ? pick_waves(shape->d_k, shape->m, round_up((L + S - 1) / S, kTile)) : kDecWaves;
+    return LOOKAT_OK;
+}
+
 extern "C" size_t lookat_attend_decode_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits)
 {
     using namespace lookat;
@@ -1190,13 +1196,12 @@ extern "C" size_t lookat_attend_decode_workspace_bytes(const lookat_shape *shape
     return (size_t)shape->B * shape->H * S * (shape->d_k + 2) * sizeof(float);
 }
 
-extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const float *lut, const uint8_t *codes,
-                                    int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale,
-                                    int32_t num_splits, void *workspace, size_t workspace_bytes, float *out,
-                                    float *scores_out, void *stream)
+namespace lookat {
+static int attend_decode_impl(const lookat_shape *shape, int64_t L, const float *lut, const uint8_t *codes,
+                              int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale,
+                              int32_t num_splits, void *workspace, size_t workspace_bytes, float *out,
+                              float *scores_out, void *stream)
 {
-    using namespace lookat;
-    clear_error();
     if (int rc = check_shape(shape))
         return rc;
     if (L <= 0)
@@ -1271,8 +1276,6 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
         case 64:
             if (waves == 16)
                 launch_tuned<64, 16, 8>(a, grid, st);
-            else if (waves == 8)
-                launch_tuned<64, 8, 8>(a, grid, st);
             else
                 launch_tuned<64, 4, 4>(a, grid, st);
             break;
@@ -1299,6 +1302,19 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
         return check_launch("lookat_attend_decode (combine kernel)");
     }
     return LOOKAT_OK;
+}
+
+}  // namespace lookat
+
+extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const float *lut, const uint8_t *codes,
+                                    int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale,
+                                    int32_t num_splits, void *workspace, size_t workspace_bytes, float *out,
+                                    float *scores_out, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    return attend_decode_impl(shape, L, lut, codes, code_stride_bh, values, value_stride_bh, scale, num_splits, workspace,
+                              workspace_bytes, out, scores_out, stream);
 }
 
 extern "C" size_t lookat_attend_decode_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L,

@@ -268,7 +268,7 @@ bool launch_encode_filter(const lookat_shape *s, int64_t N, const void *keys, in
 
 }  // namespace lookat
 
-extern "C" int lookat_encode_keys(const lookat_shape *shape, int64_t N, const void *keys, int key_dtype,
+extern "C" int lookat_encode_keys(const lookat_shape *shape, int64_t N, const void *keys, lookat_dtype key_dtype,
                                   const float *codebooks, uint8_t *codes, int64_t code_stride_bh, void *stream)
 {
     using namespace lookat;

@@ -270,7 +270,7 @@ static void launch_build_lut(const lookat_shape *s, int T, const void *q, const 
 
 }  // namespace lookat
 
-extern "C" int lookat_build_lut(const lookat_shape *shape, int32_t T, const void *q, int q_dtype,
+extern "C" int lookat_build_lut(const lookat_shape *shape, int32_t T, const void *q, lookat_dtype q_dtype,
                                 const float *codebooks, float *lut, void *stream)
 {
     using namespace lookat;

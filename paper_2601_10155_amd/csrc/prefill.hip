@@ -438,15 +438,12 @@ static int launch_prefill(const PrefillArgs &a0, int BH, hipStream_t st)
     const size_t lds = pf_table_bytes(M) + 2 * (size_t)kPfTQ * DK * sizeof(float);   // two table buffers, two tiles of queries
     auto kern = score_prefill_kernel<QT, DK, M>;
     if (lds > 64 * 1024) {
-        static bool configured = false;   // per instantiation: allow more than 64 KB of dynamic LDS
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess)
-                return fail(LOOKAT_ERR_HIP, "lookat_score_prefill: cannot reserve %zu bytes of LDS: %s", lds,
-                            hipGetErrorString(e));
-            configured = true;
-        }
+        // allow more than 64 KB of dynamic LDS: idempotent, so every call makes it (no flag shared between host threads)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return fail(LOOKAT_ERR_HIP, "lookat_score_prefill: cannot reserve %zu bytes of LDS: %s", lds,
+                        hipGetErrorString(e));
     }
     dim3 grid((unsigned)((BH + 7) / 8 * 8 * a.groups));
     hipLaunchKernelGGL(kern, grid, dim3(kPfWgThreads), lds, st, a);
@@ -475,7 +472,7 @@ static int dispatch_prefill(const lookat_shape *s, const PrefillArgs &a, hipStre
 
 }  // namespace lookat
 
-extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_t L, const void *q, int q_dtype,
+extern "C" int lookat_score_prefill(const lookat_shape *shape, int32_t T, int64_t L, const void *q, lookat_dtype q_dtype,
                                     const float *codebooks, const uint8_t *codes, int64_t code_stride_bh,
                                     float *scores, void *stream)
 {

@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Largest |gpu - oracle| seen per kind of comparison (tests/bars.py keeps the record)."""
+    try:
+        import bars
+    except Exception:
+        return
+    if bars.observed:
+        terminalreporter.write_line("largest deviations from the oracle in this run:")
+        for label in sorted(bars.observed):
+            terminalreporter.write_line(f"  {label}: {bars.observed[label]:.3e}")

@@ -11,11 +11,9 @@ import torch
 
 import lookat_inputs as li
 import oracle
+from bars import OUT_ATOL, REL, assert_out_close, record
 
 pytestmark = pytest.mark.gpu
-
-OUT_ATOL = 2e-3
-REL = 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -58,7 +56,44 @@ def _check_decode_slabs(cfg, case, cb, codes, lut, out, scale, picks):
         _lut_close(_slab(lut, b, h).reshape(lut_ref.shape), _slab(case["q"], b, h), cbn[h:h + 1], lut_ref)
         out_ref = oracle.attend_decode(lut_ref[:, :, 0], codes_ref, _slab(case["values"], b, h), scale)
         err = np.max(np.abs(_slab(out, b, h) - out_ref))
+        record(f"{cfg.name} full size, three calls", err)
         assert err <= OUT_ATOL, f"slab {(b, h)}: {err}"
+
+
+def _plant_aligned(cfg, case, cb, seed):
+    """The inputs of the fused step with the appended key planted on a far centroid and the query pointing at
+    it (see tests/test_gpu_parity.py, fused decode step): centroid 255 of every subspace := u_h (+-8 per
+    coordinate), k_new := u_h, q := beta * u_h with beta from the size of the context.  Returns (cb, k_new, q)
+    as device tensors; `case["keys"]` row L-1 is overwritten so that the cache can be re-encoded."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    u = (torch.randint(0, 2, (cfg.H, cfg.d_k), generator=gen, device="cuda").float() * 16 - 8)
+    cb = cb.clone()
+    cb[:, :, 255] = u.view(cfg.H, cfg.m, cfg.d_k // cfg.m)
+    kd = case["keys"].dtype
+    case["keys"][:, :, -1] = u[None].to(kd)
+    scale = 1.0 / math.sqrt(cfg.d_k)
+    beta = math.log(cfg.L / 0.33) / (scale * 64.0 * cfg.d_k)      # row L-1 leads every other key by about |u|^2
+    q = (beta * u)[None].expand(cfg.B, cfg.H, cfg.d_k).to(kd).contiguous()
+    k_new = case["keys"][:, :, -1].contiguous()
+    return cb, k_new, q
+
+
+def _check_step_slabs(cfg, case, cb, cache, q, k_new, out, scale, picks, label, aligned=False):
+    """The fused step's outputs on sampled (b,h) slabs against the oracle's three steps.  `cache` is the code
+    cache after the step; its rows 0..L-2 were checked against the oracle elsewhere (or are checked by the
+    caller), row L-1 is checked here."""
+    cbn = cb.cpu().numpy()
+    for b, h in picks:
+        codes_slab = _slab(cache, b, h)
+        new_ref = oracle.encode_keys(_slab(k_new[:, :, None], b, h), cbn[h:h + 1])
+        assert np.array_equal(codes_slab[:, :, -1:], new_ref), f"appended code row of slab {(b, h)}"
+        lut_ref = oracle.build_lut(_slab(q[:, :, None], b, h), cbn[h:h + 1])[:, :, 0]
+        out_ref, s_ref, alpha = oracle.attend_decode(lut_ref, codes_slab, _slab(case["values"], b, h), scale,
+                                                     want_scores=True, want_alpha=True)
+        if aligned:
+            assert 0.5 < alpha[0, 0, -1] < 0.99, f"weight of the appended key {alpha[0, 0, -1]}"
+        assert_out_close(_slab(out, b, h), out_ref, label, s_ref, scale)
 
 
 def test_config_c2_full_size_fused_step_and_three_calls(lk):
@@ -76,10 +111,27 @@ def test_config_c2_full_size_fused_step_and_three_calls(lk):
     # the fused step on a cache whose last row is stale must land on the same codes and outputs
     cache = codes.clone()
     cache[:, :, -1] = 0xEE
-    out1 = lk.lookat_decode_step(case["q"][:, :, 0].float(), case["keys"][:, :, -1].contiguous(), cb, cache,
-                                 case["values"], scale)
+    q1, k1 = case["q"][:, :, 0].float(), case["keys"][:, :, -1].contiguous()
+    out1 = lk.lookat_decode_step(q1, k1, cb, cache, case["values"], scale)
     assert torch.equal(cache, codes)
     assert float((out1 - out).abs().max()) <= 1e-5
+    _check_step_slabs(cfg, case, cb, cache, q1, k1, out1, scale, picks, "C2 full size, fused step, recipe queries")
+    # a peaked softmax (queries times 8), then the appended key carrying most of the weight
+    cache[:, :, -1] = 0xEE
+    out8 = lk.lookat_decode_step(q1 * 8, k1, cb, cache, case["values"], scale)
+    assert torch.equal(cache, codes)
+    _check_step_slabs(cfg, case, cb, cache, q1 * 8, k1, out8, scale, picks, "C2 full size, fused step, peaked queries")
+    cb_a, k_a, q_a = _plant_aligned(cfg, case, cb, 77)
+    codes_a = lk.lookat_encode_keys(case["keys"], cb_a)
+    cache = codes_a.clone()
+    cache[:, :, -1] = 0xEE
+    out_a = lk.lookat_decode_step(q_a, k_a, cb_a, cache, case["values"], scale)
+    assert torch.equal(cache, codes_a)
+    cbn = cb_a.cpu().numpy()
+    for b, h in picks:   # the re-encoded cache of the sampled slabs against the oracle
+        assert np.array_equal(_slab(codes_a, b, h), oracle.encode_keys(_slab(case["keys"], b, h), cbn[h:h + 1]))
+    _check_step_slabs(cfg, case, cb_a, cache, q_a, k_a, out_a, scale, picks, "C2 full size, fused step, aligned key",
+                      aligned=True)
 
 
 def test_config_c1_full_size(lk):
@@ -105,7 +157,9 @@ def test_config_c3_full_size_long_context(lk):
     codes = lk.lookat_encode_keys(case["keys"], cb)
     lut = lk.lookat_build_lut(case["q"], cb)
     assert lk.attend_decode_auto_splits(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L) == 1
-    out = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale)
+    assert lk.attend_decode_launch_shape(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, 0) == (1, 16)
+    scores = torch.empty((cfg.B, cfg.H, cfg.L), dtype=torch.float32, device="cuda")
+    out = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale, scores_out=scores)
     assert torch.isfinite(out).all()
     out2 = lk.lookat_attend_decode(lut.view(cfg.B, cfg.H, cfg.m, 256), codes, case["values"], scale, num_splits=2)
     assert float((out2 - out).abs().max()) <= 1e-5
@@ -120,16 +174,36 @@ def test_config_c3_full_size_long_context(lk):
         assert np.array_equal(got_codes[:, :, idx], codes_ref)
         # attention over the whole slab, from the GPU's (sample-checked) codes
         lut_ref = oracle.build_lut(_slab(case["q"], b, h), cbn[h:h + 1])
-        out_ref = oracle.attend_decode(lut_ref[:, :, 0], got_codes, _slab(case["values"], b, h), scale)
+        out_ref, s_ref = oracle.attend_decode(lut_ref[:, :, 0], got_codes, _slab(case["values"], b, h), scale,
+                                              want_scores=True)
         assert np.max(np.abs(_slab(out, b, h) - out_ref)) <= OUT_ATOL
+        # both sides from ONE table (the GPU's, within 1e-4 of the oracle's by the check in _lut_close):
+        # scores element by element and the output at the arithmetic bar, for the 16-wavefront instance
+        lut_gpu = _slab(lut, b, h)[:, :, 0]
+        _lut_close(_slab(lut, b, h), _slab(case["q"], b, h), cbn[h:h + 1], lut_ref)
+        o_ref, sc_ref = oracle.attend_decode(lut_gpu, got_codes, _slab(case["values"], b, h), scale, want_scores=True)
+        assert_out_close(_slab(out, b, h), o_ref, "C3 full size, attend_decode (16-wavefront instance)", sc_ref, scale)
+        mag = np.abs(lut_gpu[0, 0])[np.arange(cfg.m)[None, :], got_codes[0, 0].astype(np.int64)].sum(-1)
+        err = np.abs(scores[b, h].cpu().numpy().astype(np.float64) - sc_ref[0, 0])
+        assert np.all(err <= REL * np.maximum(mag, 1e-6)), f"slab {(b, h)}: score err {err.max()}"
     # the fused step (what bench.py times at this shape: B*H = 256 workgroups, one range each) on a cache
     # whose last row is stale lands on the same codes and, up to the order of the partial sums, outputs
     cache = codes.clone()
     cache[:, :, -1] = 0xEE
-    out1 = lk.lookat_decode_step(case["q"][:, :, 0].to(case["keys"].dtype).contiguous(),
-                                 case["keys"][:, :, -1].contiguous(), cb, cache, case["values"], scale)
+    q1, k1 = case["q"][:, :, 0].to(case["keys"].dtype).contiguous(), case["keys"][:, :, -1].contiguous()
+    out1 = lk.lookat_decode_step(q1, k1, cb, cache, case["values"], scale)
     assert torch.equal(cache, codes)
     assert float((out1 - out).abs().max()) <= 1e-5
+    # peaked softmax, then the appended key carrying most of the weight, at the arithmetic bar
+    cache[:, :, -1] = 0xEE
+    out8 = lk.lookat_decode_step(q1 * 8, k1, cb, cache, case["values"], scale)
+    assert torch.equal(cache, codes)
+    _check_step_slabs(cfg, case, cb, cache, q1 * 8, k1, out8, scale, picks, "C3 full size, fused step, peaked queries")
+    cb_a, k_a, q_a = _plant_aligned(cfg, case, cb, 78)
+    cache[:, :, -1] = 0xEE          # (rows 0..L-2 keep the codes of the unplanted codebook: a valid cache all the same)
+    out_a = lk.lookat_decode_step(q_a, k_a, cb_a, cache, case["values"], scale)
+    _check_step_slabs(cfg, case, cb_a, cache, q_a, k_a, out_a, scale, picks, "C3 full size, fused step, aligned key",
+                      aligned=True)
 
 
 def test_config_c3_full_size_grouped_queries(lk):

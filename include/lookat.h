@@ -142,6 +142,30 @@ int lookat_attend_decode(const lookat_shape *shape, int64_t L,
                          void *stream);
 
 /*
+ * lookat_attend_decode for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error behaviour as lookat_attend_decode, without `workspace`: the
+ * per-range partial results live in LOOKAT_NOALLOC_SCRATCH_BYTES of device memory that is part of
+ * the library's own image (every GPU the library runs on holds one copy until the process ends;
+ * its address is looked up on the first call on a device).  The call allocates and frees nothing.
+ *   - Problems that need more than that (B*H*ranges*(d_k+2) floats, see
+ *     lookat_attend_decode_workspace_bytes): LOOKAT_ERR_WORKSPACE, nothing enqueued.
+ *   - All calls on one GPU share the memory: two calls whose kernels may overlap on one GPU
+ *     (different streams, no ordering between them) race.  Calls on one stream do not.
+ *   - Nothing in it needs a defined value before a call: every partial result that is read was
+ *     written by the same call.
+ */
+#define LOOKAT_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)
+
+int lookat_attend_decode_noalloc(const lookat_shape *shape, int64_t L,
+                                 const float *lut,
+                                 const uint8_t *codes, int64_t code_stride_bh,
+                                 const void *values, int64_t value_stride_bh,
+                                 float scale, int32_t num_splits,
+                                 float *out, float *scores_out,
+                                 void *stream);
+
+/*
  * Attention decode with grouped queries (the combination with grouped-query attention that the
  * paper names as future work, Sec. "Future Work"; sharing of key/value heads: Sec. "Structural
  * Approaches"): `group` consecutive query heads share one key/value head.  Per query head the

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     load_library,
     lookat_attend_decode,
     lookat_attend_decode_gqa,
+    lookat_attend_decode_noalloc,
     lookat_build_lut,
     lookat_decode_step,
     lookat_decode_step_split,
@@ -36,6 +37,6 @@ from .binding import (  # noqa: F401
 __all__ = [
     "LookatError", "attend_decode", "attend_decode_auto_splits", "attend_decode_launch_shape", "attend_decode_gqa_workspace_bytes", "attend_decode_workspace_bytes",
     "build_lut", "encode_keys", "last_error", "lib_path", "load_library", "version",
-    "lookat_attend_decode", "lookat_attend_decode_gqa", "lookat_build_lut", "lookat_decode_step", "lookat_decode_step_split", "lookat_decode_step_gqa", "decode_step_split_workspace_bytes", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
+    "lookat_attend_decode", "lookat_attend_decode_gqa", "lookat_attend_decode_noalloc", "lookat_build_lut", "lookat_decode_step", "lookat_decode_step_split", "lookat_decode_step_gqa", "decode_step_split_workspace_bytes", "lookat_encode_keys", "lookat_kmeans", "lookat_kmeans_step",
     "lookat_probe_stream_read", "lookat_probe_stream_write", "lookat_score_prefill",
 ]

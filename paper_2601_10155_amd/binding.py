@@ -56,6 +56,8 @@ def load_library():
         lib.lookat_attend_decode_launch_shape.restype = ctypes.c_int
         lib.lookat_attend_decode.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
         lib.lookat_attend_decode.restype = ctypes.c_int
+        lib.lookat_attend_decode_noalloc.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, vp, vp]
+        lib.lookat_attend_decode_noalloc.restype = ctypes.c_int
         lib.lookat_attend_decode_gqa_workspace_bytes.argtypes = [sp, i32, i64, i32]
         lib.lookat_attend_decode_gqa_workspace_bytes.restype = sz
         lib.lookat_attend_decode_gqa.argtypes = [sp, i32, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp, vp]
@@ -245,6 +247,26 @@ def lookat_attend_decode(lut: torch.Tensor, codes: torch.Tensor, values: torch.T
                                     values.data_ptr(), vs, float(scale), int(num_splits), ws_ptr, ws_bytes,
                                     out.data_ptr(), scores_out.data_ptr() if scores_out is not None else None,
                                     _stream(values)))
+    return out
+
+
+def lookat_attend_decode_noalloc(lut: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,
+                                 out: torch.Tensor, num_splits: int = 0,
+                                 scores_out: torch.Tensor | None = None) -> torch.Tensor:
+    """lookat_attend_decode without a workspace (the library's own scratch memory): for callers that
+    cannot allocate.  `out` [B,H,d_k] fp32 must be given; nothing is allocated here or in the library."""
+    lib = load_library()
+    _dev(lut, "lut"), _dev(codes, "codes"), _dev(values, "values"), _dev(out, "out")
+    shape, L = _decode_shape(lut, codes, values)
+    if out.dtype != torch.float32 or out.numel() != shape.B * shape.H * shape.d_k or not out.is_contiguous():
+        raise ValueError("out must be contiguous fp32 [B,H,d_k]")
+    if scores_out is not None and (scores_out.dtype != torch.float32 or scores_out.numel() != shape.B * shape.H * L
+                                   or not scores_out.is_contiguous()):
+        raise ValueError("scores_out must be contiguous fp32 [B,H,L]")
+    _check(lib.lookat_attend_decode_noalloc(ctypes.byref(shape), L, lut.data_ptr(), codes.data_ptr(),
+                                            _bh_stride(codes, "codes"), values.data_ptr(), _bh_stride(values, "values"),
+                                            float(scale), int(num_splits), out.data_ptr(),
+                                            scores_out.data_ptr() if scores_out is not None else None, _stream(values)))
     return out
 
 

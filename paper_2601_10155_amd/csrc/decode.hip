@@ -12,6 +12,7 @@
 //     (online softmax), so the streaming loop has no workgroup barrier;
 //   * the sequence is cut into `splits` ranges per (b,h) (flash-decoding style); the
 //     ranges are merged by a second small kernel.
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -1304,6 +1305,34 @@ static int attend_decode_impl(const lookat_shape *shape, int64_t L, const float 
     return LOOKAT_OK;
 }
 
+// Scratch memory of lookat_attend_decode_noalloc: the per-range partial results, in the library's own
+// device image instead of a caller's workspace.  Every GPU the library runs on holds one copy.
+static __device__ __align__(256) float scratch[LOOKAT_NOALLOC_SCRATCH_BYTES / sizeof(float)];
+
+// Device address of `scratch` on the current device (in host code the array's name is only a handle
+// for this query), looked up once per device and kept.
+static int scratch_address(float **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static float *known[kMaxDevices] = {};
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess || device < 0 || device >= kMaxDevices)
+        return fail(LOOKAT_ERR_HIP, "lookat_attend_decode_noalloc: cannot identify the current device (%s, device %d)",
+                    hipGetErrorString(e), device);
+    std::lock_guard<std::mutex> hold(lock);
+    if (!known[device]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(LOOKAT_ERR_HIP, "lookat_attend_decode_noalloc: hipGetSymbolAddress failed on device %d: %s", device,
+                        hipGetErrorString(e));
+        known[device] = static_cast<float *>(p);
+    }
+    *ptr = known[device];
+    return LOOKAT_OK;
+}
 }  // namespace lookat
 
 extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const float *lut, const uint8_t *codes,
@@ -1315,6 +1344,32 @@ extern "C" int lookat_attend_decode(const lookat_shape *shape, int64_t L, const 
     clear_error();
     return attend_decode_impl(shape, L, lut, codes, code_stride_bh, values, value_stride_bh, scale, num_splits, workspace,
                               workspace_bytes, out, scores_out, stream);
+}
+
+extern "C" int lookat_attend_decode_noalloc(const lookat_shape *shape, int64_t L, const float *lut, const uint8_t *codes,
+                                            int64_t code_stride_bh, const void *values, int64_t value_stride_bh,
+                                            float scale, int32_t num_splits, float *out, float *scores_out, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (L <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
+    if (num_splits < 0 || num_splits > 65535)
+        return fail(LOOKAT_ERR_SHAPE, "num_splits=%d out of range [0,65535]", num_splits);
+    const size_t need = lookat_attend_decode_workspace_bytes(shape, L, num_splits);
+    if (need > (size_t)LOOKAT_NOALLOC_SCRATCH_BYTES)
+        return fail(LOOKAT_ERR_WORKSPACE,
+                    "lookat_attend_decode_noalloc: B*H*ranges*(d_k+2) floats = %zu bytes exceed the library's %d bytes of "
+                    "scratch memory; use lookat_attend_decode with a workspace", need, (int)LOOKAT_NOALLOC_SCRATCH_BYTES);
+    float *ws = nullptr;
+    if (need) {   // (one range per (b,h): no partial results, nothing to look up)
+        if (int rc = scratch_address(&ws))
+            return rc;
+    }
+    return attend_decode_impl(shape, L, lut, codes, code_stride_bh, values, value_stride_bh, scale, num_splits, ws,
+                              need ? (size_t)LOOKAT_NOALLOC_SCRATCH_BYTES : 0, out, scores_out, stream);
 }
 
 extern "C" size_t lookat_attend_decode_gqa_workspace_bytes(const lookat_shape *shape, int32_t group, int64_t L,

@@ -12,6 +12,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "lookat.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -34,6 +36,53 @@ int lookat_probe_stream_read(const void *src, size_t bytes, uint32_t *sink, void
  * `stream`.  Returns 0, or a negative lookat_status from lookat.h.
  */
 int lookat_probe_stream_write(void *dst, size_t bytes, uint32_t word, void *stream);
+
+/*
+ * The read stream in a chosen launch shape, to look for the shape that streams a buffer fastest (the
+ * ceiling a streaming kernel is judged against must not share that kernel's launch head and tail):
+ *   threads           workgroup size: 64, 128, 256, 512 or 1024
+ *   loads_per_thread  16-byte loads a thread keeps in flight per round: 1, 2, 4, 8 or 16
+ *   workgroups        0: as many as cover the buffer in one round (every thread reads once);
+ *                     > 0: that many persistent workgroups
+ *   contiguous        persistent workgroups only: 0 = rounds strided by the grid (at any time the grid
+ *                     reads one contiguous window), 1 = every workgroup owns one contiguous share
+ *   nontemporal       1 = loads carry the read-once hint
+ * Other arguments and behaviour as lookat_probe_stream_read.  LOOKAT_ERR_UNSUPPORTED for other values.
+ */
+int lookat_probe_stream_read_shaped(const void *src, size_t bytes, uint32_t *sink, int32_t threads,
+                                    int32_t loads_per_thread, int32_t workgroups, int32_t contiguous,
+                                    int32_t nontemporal, void *stream);
+
+/* A kernel that does nothing, `workgroups` x `threads`: back-to-back launches of it on one stream give the
+ * launch interval of the device and runtime (the floor under any per-launch time measured that way). */
+int lookat_probe_empty_launch(int32_t workgroups, int32_t threads, void *stream);
+
+/*
+ * lookat_attend_decode (paper Algorithm 1 after the table build; same arguments, same result) on a flat
+ * launch geometry with the pieces of a (b,h) merged INSIDE the kernel: the 64-key tiles of all (b,h) form
+ * one index space cut into equal shares, one per workgroup (a share may hold the tail of one (b,h), a whole
+ * one and the head of the next); every piece of a shared (b,h) publishes (o, max, sum) in the workspace and
+ * draws a ticket from that (b,h)'s counter, the last ticket merges and writes `out`.  num_splits = 0: equal
+ * shares over the 256 compute units; >= 1: shares of ceil(tiles / num_splits) tiles.
+ * A measurement aid: lookat_attend_decode (one range per workgroup, a second launch to merge) measured
+ * faster on MI355X at every workload; this entry point keeps that comparison reproducible.
+ *   workspace        lookat_probe_attend_decode_ticket_workspace_bytes() bytes, 16-byte aligned; its first
+ *                    256-byte-rounded 4*B*H bytes are the ticket counters: ZERO them once after allocation
+ *                    and whenever B*H changes (the kernel leaves them at zero)
+ *   pieces_per_unit  host pointer or NULL: receives the most pieces a (b,h) is cut into
+ * Supported: d_k in {32, 64, 128, 256}, m in {2, 4, 8, 16}.
+ */
+size_t lookat_probe_attend_decode_ticket_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits);
+
+int lookat_probe_attend_decode_ticket(const lookat_shape *shape, int64_t L,
+                                      const float *lut,
+                                      const uint8_t *codes, int64_t code_stride_bh,
+                                      const void *values, int64_t value_stride_bh,
+                                      float scale, int32_t num_splits,
+                                      void *workspace, size_t workspace_bytes,
+                                      float *out, float *scores_out,
+                                      int32_t *pieces_per_unit,
+                                      void *stream);
 
 #ifdef __cplusplus
 }

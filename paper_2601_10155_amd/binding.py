@@ -80,6 +80,15 @@ def load_library():
         lib.lookat_probe_stream_read.restype = ctypes.c_int
         lib.lookat_probe_stream_write.argtypes = [vp, sz, ctypes.c_uint32, vp]
         lib.lookat_probe_stream_write.restype = ctypes.c_int
+        lib.lookat_probe_stream_read_shaped.argtypes = [vp, sz, vp, i32, i32, i32, i32, i32, vp]
+        lib.lookat_probe_stream_read_shaped.restype = ctypes.c_int
+        lib.lookat_probe_empty_launch.argtypes = [i32, i32, vp]
+        lib.lookat_probe_empty_launch.restype = ctypes.c_int
+        lib.lookat_probe_attend_decode_ticket_workspace_bytes.argtypes = [sp, i64, i32]
+        lib.lookat_probe_attend_decode_ticket_workspace_bytes.restype = sz
+        lib.lookat_probe_attend_decode_ticket.argtypes = [sp, i64, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp,
+                                                          ctypes.POINTER(i32), vp]
+        lib.lookat_probe_attend_decode_ticket.restype = ctypes.c_int
         lib.lookat_last_error.restype = ctypes.c_char_p
         lib.lookat_version.restype = ctypes.c_int
         _lib = lib
@@ -480,6 +489,54 @@ def lookat_probe_stream_write(dst: torch.Tensor, word: int = 0) -> None:
         raise ValueError("dst must be contiguous")
     _check(lib.lookat_probe_stream_write(dst.data_ptr(), dst.numel() * dst.element_size(), int(word) & 0xffffffff,
                                          _stream(dst)))
+
+
+def lookat_probe_stream_read_shaped(src: torch.Tensor, sink: torch.Tensor, threads: int, loads_per_thread: int,
+                                    workgroups: int = 0, contiguous: bool = False, nontemporal: bool = True) -> None:
+    """Measurement aid: the read stream in a chosen launch shape (see include/lookat_probe.h)."""
+    lib = load_library()
+    _dev(src, "src"), _dev(sink, "sink")
+    if not src.is_contiguous():
+        raise ValueError("src must be contiguous")
+    _check(lib.lookat_probe_stream_read_shaped(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                               int(threads), int(loads_per_thread), int(workgroups), int(bool(contiguous)),
+                                               int(bool(nontemporal)), _stream(src)))
+
+
+def lookat_probe_empty_launch(workgroups: int, threads: int) -> None:
+    """Measurement aid: launches a kernel that does nothing on the current stream."""
+    _check(load_library().lookat_probe_empty_launch(int(workgroups), int(threads),
+                                                    torch.cuda.current_stream().cuda_stream))
+
+
+def probe_attend_decode_ticket_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, num_splits: int = 0) -> int:
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_probe_attend_decode_ticket_workspace_bytes(ctypes.byref(shape), L, num_splits))
+
+
+def lookat_probe_attend_decode_ticket(lut: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,
+                                      num_splits: int = 0, workspace: torch.Tensor | None = None,
+                                      out: torch.Tensor | None = None, scores_out: torch.Tensor | None = None):
+    """Measurement aid: lookat_attend_decode on the flat geometry with the in-kernel ticket merge.
+    Returns (out, pieces per (b,h)).  A workspace allocated here is zeroed (its ticket counters must be)."""
+    lib = load_library()
+    _dev(lut, "lut"), _dev(codes, "codes"), _dev(values, "values")
+    shape, L = _decode_shape(lut, codes, values)
+    B, H, d_k = shape.B, shape.H, shape.d_k
+    need = int(lib.lookat_probe_attend_decode_ticket_workspace_bytes(ctypes.byref(shape), L, num_splits))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.zeros(need, dtype=torch.uint8, device=values.device)
+    if out is None:
+        out = torch.empty((B, H, d_k), dtype=torch.float32, device=values.device)
+    pieces = ctypes.c_int32(0)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.lookat_probe_attend_decode_ticket(ctypes.byref(shape), L, lut.data_ptr(), codes.data_ptr(),
+                                                 _bh_stride(codes, "codes"), values.data_ptr(), _bh_stride(values, "values"),
+                                                 float(scale), int(num_splits), ws_ptr, ws_bytes, out.data_ptr(),
+                                                 scores_out.data_ptr() if scores_out is not None else None,
+                                                 ctypes.byref(pieces), _stream(values)))
+    return out, int(pieces.value)
 
 
 # short aliases

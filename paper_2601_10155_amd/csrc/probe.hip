@@ -44,7 +44,119 @@ __global__ __launch_bounds__(kProbeThreads) void stream_write_kernel(uint4 *__re
     }
 }
 
+__global__ void empty_kernel(uint32_t *never)
+{
+    if (never && threadIdx.x == 0x7fffffffu)
+        never[0] = 1u;
+}
+
+// Persistent read: workgroups of NT threads, PER 16-byte loads per thread and round.  CONTIG = 0: rounds
+// strided by the grid; 1: every workgroup streams one contiguous share.
+template <int NT, int PER, int NTL, int CONTIG>
+__global__ __launch_bounds__(NT) void stream_read_shaped_kernel(const probe_v4u *__restrict__ p, size_t n16, uint32_t *sink)
+{
+    uint32_t x = 0;
+    const size_t chunk = (size_t)NT * PER;
+    const size_t share = CONTIG ? (n16 + gridDim.x - 1) / gridDim.x : n16;
+    const size_t s0 = CONTIG ? (size_t)blockIdx.x * share : (size_t)blockIdx.x * chunk;
+    const size_t s1 = CONTIG ? ((s0 + share < n16) ? s0 + share : n16) : n16;
+    const size_t step = CONTIG ? chunk : (size_t)gridDim.x * chunk;
+    for (size_t base = s0; base < s1; base += step) {
+        probe_v4u v[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const size_t i = base + (size_t)j * NT + threadIdx.x;
+            v[j] = (i < s1) ? (NTL ? __builtin_nontemporal_load(p + i) : p[i]) : probe_v4u{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j)
+            x ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+    }
+    if (x == 0x9e3779b9u)
+        sink[0] = x;
+}
+
+template <int NT, int PER>
+static void launch_shaped(int ntl, int contig, dim3 grid, hipStream_t st, const probe_v4u *p, size_t n16, uint32_t *sink)
+{
+    if (ntl && contig)
+        hipLaunchKernelGGL((stream_read_shaped_kernel<NT, PER, 1, 1>), grid, dim3(NT), 0, st, p, n16, sink);
+    else if (ntl)
+        hipLaunchKernelGGL((stream_read_shaped_kernel<NT, PER, 1, 0>), grid, dim3(NT), 0, st, p, n16, sink);
+    else if (contig)
+        hipLaunchKernelGGL((stream_read_shaped_kernel<NT, PER, 0, 1>), grid, dim3(NT), 0, st, p, n16, sink);
+    else
+        hipLaunchKernelGGL((stream_read_shaped_kernel<NT, PER, 0, 0>), grid, dim3(NT), 0, st, p, n16, sink);
+}
+
+template <int NT>
+static bool launch_shaped_per(int per, int ntl, int contig, dim3 grid, hipStream_t st, const probe_v4u *p, size_t n16,
+                              uint32_t *sink)
+{
+    switch (per) {
+    case 1: launch_shaped<NT, 1>(ntl, contig, grid, st, p, n16, sink); return true;
+    case 2: launch_shaped<NT, 2>(ntl, contig, grid, st, p, n16, sink); return true;
+    case 4: launch_shaped<NT, 4>(ntl, contig, grid, st, p, n16, sink); return true;
+    case 8: launch_shaped<NT, 8>(ntl, contig, grid, st, p, n16, sink); return true;
+    case 16: launch_shaped<NT, 16>(ntl, contig, grid, st, p, n16, sink); return true;
+    default: return false;
+    }
+}
+
 }  // namespace lookat
+
+extern "C" int lookat_probe_empty_launch(int32_t workgroups, int32_t threads, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (workgroups <= 0 || threads <= 0 || threads > 1024)
+        return fail(LOOKAT_ERR_SHAPE, "workgroups=%d threads=%d: need positive counts, at most 1024 threads", workgroups, threads);
+    hipLaunchKernelGGL(empty_kernel, dim3((unsigned)workgroups), dim3((unsigned)threads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint32_t *>(nullptr));
+    return check_launch("lookat_probe_empty_launch");
+}
+
+extern "C" int lookat_probe_stream_read_shaped(const void *src, size_t bytes, uint32_t *sink, int32_t threads,
+                                               int32_t loads_per_thread, int32_t workgroups, int32_t contiguous,
+                                               int32_t nontemporal, void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (!src || !sink)
+        return fail(LOOKAT_ERR_NULL, "src and sink must be non-NULL");
+    if (bytes == 0 || (bytes % 16))
+        return fail(LOOKAT_ERR_SHAPE, "bytes=%zu must be a positive multiple of 16", bytes);
+    if (!aligned16(src))
+        return fail(LOOKAT_ERR_ALIGN, "src must be 16-byte aligned");
+    if (workgroups < 0 || loads_per_thread <= 0 || threads <= 0)
+        return fail(LOOKAT_ERR_SHAPE, "workgroups must be >= 0, threads and loads_per_thread positive");
+    const size_t n16 = bytes / 16;
+    size_t blocks = (size_t)workgroups;
+    if (blocks == 0) {
+        const size_t per_block = (size_t)loads_per_thread * threads;
+        blocks = (n16 + per_block - 1) / per_block;
+        contiguous = 0;
+    }
+    if (blocks > 0x7fffffffULL)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "bytes=%zu exceed one launch", bytes);
+    dim3 grid((unsigned)blocks);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const probe_v4u *p = static_cast<const probe_v4u *>(src);
+    const int ntl = nontemporal ? 1 : 0, contig = contiguous ? 1 : 0;
+    bool ok = false;
+    switch (threads) {
+    case 64: ok = launch_shaped_per<64>(loads_per_thread, ntl, contig, grid, st, p, n16, sink); break;
+    case 128: ok = launch_shaped_per<128>(loads_per_thread, ntl, contig, grid, st, p, n16, sink); break;
+    case 256: ok = launch_shaped_per<256>(loads_per_thread, ntl, contig, grid, st, p, n16, sink); break;
+    case 512: ok = launch_shaped_per<512>(loads_per_thread, ntl, contig, grid, st, p, n16, sink); break;
+    case 1024: ok = launch_shaped_per<1024>(loads_per_thread, ntl, contig, grid, st, p, n16, sink); break;
+    default: break;
+    }
+    if (!ok)
+        return fail(LOOKAT_ERR_UNSUPPORTED, "threads=%d / loads_per_thread=%d: threads in {64,128,256,512,1024}, loads in {1,2,4,8,16}",
+                    threads, loads_per_thread);
+    return check_launch("lookat_probe_stream_read_shaped");
+}
 
 extern "C" int lookat_probe_stream_write(void *dst, size_t bytes, uint32_t word, void *stream)
 {

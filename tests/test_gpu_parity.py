@@ -695,6 +695,46 @@ def test_attend_decode_gqa_equals_per_head_calls(lk):
     assert float((out - ref).abs().max()) <= 1e-5
 
 
+@pytest.mark.parametrize("d_k,m", [(64, 4), (128, 8), (64, 16), (32, 2), (256, 8)])
+@pytest.mark.parametrize("B,H,L,splits", [(2, 5, 1, 0), (2, 5, 65, 3), (3, 5, 777, 40), (1, 3, 4133, 0), (2, 3, 2049, 0),
+                                          (48, 8, 200, 0), (25, 16, 130, 0), (1, 2, 9000, 5)])
+def test_ticket_merge_probe_matches_oracle(lk, d_k, m, B, H, L, splits):
+    """The measurement-aid kernel (flat geometry, pieces of a (b,h) merged in-kernel by ticket): scores and
+    outputs against the oracle on shapes that give one piece per (b,h), ranges of a (b,h), shares of one and a
+    half (b,h) (384 and 400 pairs on 256 compute units: tail + whole + head) and more ranges than tiles; two
+    calls in a row on one workspace (the counters must come back to zero)."""
+    rng = np.random.default_rng(9500 + d_k + m + B * H + L)
+    lut, codes, v = _decode_case(rng, B, H, L, d_k, m, lut_scale=6.0)
+    scale = 1.0 / math.sqrt(d_k)
+    ref, s_ref = oracle.attend_decode(lut, codes, v, scale, want_scores=True)
+    need = lk.probe_attend_decode_ticket_workspace_bytes(B, H, d_k, m, L, splits)
+    ws = torch.zeros(max(need, 16), dtype=torch.uint8, device="cuda")
+    lut_d, codes_d, v_d = dev(lut), dev(codes), dev(v)
+    for call in range(2):
+        scores = torch.empty((B, H, L), dtype=torch.float32, device="cuda")
+        out, pieces = lk.lookat_probe_attend_decode_ticket(lut_d, codes_d, v_d, scale, num_splits=splits, workspace=ws,
+                                                           scores_out=scores)
+        assert (pieces > 1) == (need > 0)
+        assert_out_close(out.cpu().numpy(), ref, "ticket-merge probe", s_ref, scale)
+        assert_scores_close(scores.cpu().numpy(), lut, codes, s_ref)
+    if need:
+        tickets = ws[: B * H * 4].view(torch.int32)
+        assert int(tickets.abs().max()) == 0, "ticket counters not back at zero"
+
+
+def test_probe_stream_read_shapes_run(lk):
+    """Every launch shape of the read probe streams the buffer without writing anything."""
+    buf = torch.arange(1 << 18, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    for threads in (64, 256, 1024):
+        for loads in (1, 8, 16):
+            for wgs, contig in ((0, False), (7, False), (7, True)):
+                lk.lookat_probe_stream_read_shaped(buf, sink, threads, loads, wgs, contig, True)
+    lk.lookat_probe_empty_launch(384, 256)
+    torch.cuda.synchronize()
+    assert int(sink.abs().max()) == 0
+
+
 def test_probe_stream_write_fills_exactly_the_buffer(lk):
     buf = torch.zeros(4096 + 8, dtype=torch.int32, device="cuda")
     lk.lookat_probe_stream_write(buf[4:4 + 4096], 0x5A5A1234)

@@ -40,7 +40,12 @@ extern "C" {
 
 typedef enum {
     LOOKAT_F16 = 1, /* IEEE binary16 */
-    LOOKAT_F32 = 2  /* IEEE binary32 */
+    LOOKAT_F32 = 2, /* IEEE binary32 */
+    /* Not dtypes.  They give the type the whole range of int, so that the library (built as C++, where an
+     * enumeration only holds values up to its largest enumerator's bit width) can test and reject any
+     * value a C caller passes: an unknown value returns LOOKAT_ERR_DTYPE. */
+    LOOKAT_DTYPE_RANGE_LOW_ = -0x7fffffff - 1,
+    LOOKAT_DTYPE_RANGE_HIGH_ = 0x7fffffff
 } lookat_dtype;
 
 typedef enum {

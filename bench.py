@@ -39,21 +39,47 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # FETCH_SIZE of lookat::stream_read_kernel in the same run, KiB that kernel reads, WRITE_SIZE
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {
-    ("C1", True): (1249.5, 776.004, 1536.0, 3.375),
-    ("C1", False): (826.5, 776.004, 1536.0, 3.0),
-    ("C2", True): (26393.0, 24584.0, 49152.0, 108.0),
-    ("C2", False): (26144.5, 24584.0, 49152.0, 96.0),
-    ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0),
-    ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0),
-    ("C4", "score_prefill"): (37033.6, 1.0, 2.0, 2.10989e6),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
+    # key: (workload, fused step?) -> (FETCH_SIZE, stream FETCH_SIZE, stream KiB, WRITE_SIZE KiB, launch shape counted)
+    # launch shape: "fused" = the 512-thread fused-step instance, one range per (b,h); else (ranges, wavefronts) of
+    # lookat_attend_decode as lookat_attend_decode_launch_shape reports them.
+    ("C1", True): (1249.5, 776.004, 1536.0, 3.375, "fused"),
+    ("C1", False): (826.5, 776.004, 1536.0, 3.0, (1, 4)),
+    ("C2", True): (26393.0, 24584.0, 49152.0, 108.0, "fused"),
+    ("C2", False): (26144.5, 24584.0, 49152.0, 96.0, (1, 4)),
+    ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0, "fused"),
+    ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0, (2, 16)),
+    ("C4", "score_prefill"): (37033.6, 1.0, 2.0, 2.10989e6, None),   # FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
 }
 
 
-def counted_traffic(key):
+def counted_traffic(key, launch_shape=None):
+    """HBM bytes per launch from the stored counter readings, or None when there is no reading for this
+    workload or the launch shape timed now is not the one the counters were read on (a stale reading)."""
     if key not in COUNTED_TRAFFIC:
         return None
-    fetch, stream_fetch, known_kib, write_kib = COUNTED_TRAFFIC[key]
+    fetch, stream_fetch, known_kib, write_kib, counted_shape = COUNTED_TRAFFIC[key]
+    if counted_shape is not None and launch_shape != counted_shape:
+        return None
     return int(round((fetch * known_kib / stream_fetch + write_kib) * 1024.0))
+
+
+def per_launch_stats(torch, fn, layers, n_launch, batches=24):
+    """Back-to-back launches timed in `batches` batches (a HIP event between batches only: an event between
+    every two launches costs the GPU about 3 us and would measure itself): per-launch mean of every batch;
+    returns the median, minimum and maximum over the batches (us per launch)."""
+    per = max(len(layers), n_launch // batches // len(layers) * len(layers))   # whole rotations over the layers' caches
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(batches + 1)]
+    for ly in layers:
+        fn(ly)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for b in range(batches):
+        for i in range(per):
+            fn(layers[i % len(layers)])
+        ev[b + 1].record()
+    torch.cuda.synchronize()
+    t = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 / per for i in range(batches))
+    return {"median": t[len(t) // 2], "min": t[0], "max": t[-1], "launches_per_batch": per, "batches": batches}
 
 
 def pick_launch_mode(mode, step, replay, trial_steps=10):
@@ -106,6 +132,10 @@ def parse_args():
     ap.add_argument("--kmeans-iters", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg")
+    ap.add_argument("--probes", action="store_true",
+                    help="also time the measurement aids on this workload's buffers and add them as \"probes\": the launch "
+                         "interval of an empty kernel, the read stream in a sweep of launch shapes, and attention with the "
+                         "in-kernel ticket merge (include/lookat_probe.h)")
     return ap.parse_args()
 
 
@@ -257,6 +287,10 @@ def main():
     us_decode_alone = time_launches(decode_only)
     us_per_launch = time_launches(fused_only) if fused else us_decode_alone
     achieved = bytes_per_launch / us_per_launch / 1e3   # GB/s
+    stats = per_launch_stats(torch, fused_only if fused else decode_only, layers, n_launch)
+    stats_alone = per_launch_stats(torch, decode_only, layers, n_launch) if fused else stats
+    launch_shape = "fused" if (fused and not fused_split) else \
+        (None if fused else lk.attend_decode_launch_shape(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, splits))
 
     # plain read stream over the same value caches: what the HBM read path delivers here
     sink = torch.zeros(4, dtype=torch.int32, device=device)
@@ -270,6 +304,10 @@ def main():
     torch.cuda.synchronize()
     stream_us = e0.elapsed_time(e1) * 1e3 / n_launch
     stream_gbs = layers[0].values.numel() * 2 / stream_us / 1e3
+
+    probes = None
+    if args.probes:
+        probes = run_probes(torch, lk, cfg, layers, scale, sink, time_launches, n_launch)
 
     result = {
         "metric": "LUT-attention decode keys scored/sec/GPU; achieved HBM GB/s vs peak",
@@ -301,20 +339,78 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None if args.batch else counted_traffic((cfg.name, fused)),
+            "traffic": None if args.batch else counted_traffic((cfg.name, fused), launch_shape),
             "bytes_per_launch": bytes_per_launch,
             "us_per_launch": us_per_launch,
+            "us_per_launch_median": stats["median"],
+            "us_per_launch_min": stats["min"],
+            "us_per_launch_max": stats["max"],
+            "median_min_max_over": f"{stats['batches']} batches of {stats['launches_per_batch']} back-to-back launches",
             "launches_timed": n_launch,
             "attend_decode_alone_us": us_decode_alone,
+            "attend_decode_alone_us_median": stats_alone["median"],
+            "attend_decode_alone_us_min": stats_alone["min"],
             "attend_decode_alone_GBs": bytes_per_launch / us_decode_alone / 1e3,
             "read_stream_GBs": stream_gbs,
             "frac_of_read_stream": achieved / stream_gbs,
         },
     }
 
+    if probes is not None:
+        result["probes"] = probes
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, layers, scale, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def run_probes(torch, lk, cfg, layers, scale, sink, time_launches, n_launch):
+    """The measurement aids on this workload's buffers (per-launch microseconds, back to back on one stream)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def loop(fn, n):
+        fn(0)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    out = {"empty_launch_us": {f"{wg}x{th}": loop(lambda i: lk.lookat_probe_empty_launch(wg, th), 2000)
+                               for wg, th in ((1, 256), (cfg.B * cfg.H, 256), (4 * cfg.B * cfg.H, 256))}}
+    vbytes = layers[0].values.numel() * 2
+    shapes = [(256, 2, 0, False), (256, 1, 0, False), (256, 4, 0, False), (512, 2, 0, False), (128, 2, 0, False),
+              (256, 8, 768, False), (256, 8, 1536, False), (512, 8, 512, False), (1024, 8, 256, False), (1024, 4, 256, False),
+              (256, 8, 768, True), (512, 8, 512, True), (1024, 8, 256, True), (256, 16, 768, False)]
+    sweep = {}
+    for th, loads, wgs, contig in shapes:
+        us = loop(lambda i: lk.lookat_probe_stream_read_shaped(layers[i % len(layers)].values, sink, th, loads, wgs, contig, True),
+                  n_launch // 4)
+        sweep[f"{th} threads x {loads} loads, " + (f"{wgs} persistent workgroups" + (", contiguous shares" if contig else ", grid-strided")
+                                                    if wgs else "one round")] = round(vbytes / us / 1e3, 1)
+    out["read_stream_GBs_by_launch_shape"] = sweep
+    out["read_stream_best_GBs"] = max(sweep.values())
+    # attention with the in-kernel ticket merge against the two-launch path, ranges chosen by each
+    ws = torch.zeros(max(16, lk.probe_attend_decode_ticket_workspace_bytes(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, 0)),
+                     dtype=torch.uint8, device=layers[0].values.device)
+    pieces = {}
+
+    def ticket(ly, splits=0):
+        _, pieces[splits] = lk.lookat_probe_attend_decode_ticket(ly.lut.view(cfg.B, cfg.H, cfg.m, cfg.K), ly.codes, ly.values,
+                                                                  scale, num_splits=splits, workspace=ws, out=ly.out)
+
+    ref = lk.lookat_attend_decode(layers[0].lut.view(cfg.B, cfg.H, cfg.m, cfg.K), layers[0].codes, layers[0].values, scale).clone()
+    ticket(layers[0])
+    torch.cuda.synchronize()
+    out["ticket_merge"] = {
+        "us_per_launch_equal_shares": time_launches(ticket),
+        "pieces_per_bh_equal_shares": pieces[0],
+        "max_abs_diff_vs_lookat_attend_decode": float((layers[0].out - ref).abs().max()),
+    }
+    if cfg.B * cfg.H >= 256:   # the same kernel with one whole (b,h) per workgroup: nothing to merge
+        out["ticket_merge"]["us_per_launch_one_range"] = time_launches(lambda ly: ticket(ly, 1))
+    return out
 
 
 def gqa_main(args, cfg, lk, li, torch, device):
@@ -560,50 +656,69 @@ def prefill_cpu_baseline(cfg, keys, q, cb, codes, scores, budget_s):
 
 def cpu_baseline(cfg, layers, scale, budget_s):
     """The CPU oracle as it stands, on the same arrays the GPU consumed: the same three calls
-    (encode the new key, build the tables, attend) on whole (b,h) slabs of the first layer,
-    as many batch entries as fit the time budget.  Also checks the GPU output on that sample."""
+    (encode the new key, build the tables, attend) on whole (b,h) slabs of the first layer, as many
+    (b,h) pairs as fit the time budget, on all host cores (OpenMP over (b,h)) and on one thread.
+    Also checks the GPU output on that sample."""
     import numpy as np
 
     import oracle
 
     ly = layers[0]
-    nb = cfg.B
-    codes = ly.codes.cpu().numpy()
-    values = ly.values.cpu().numpy()
-    q = ly.q.cpu().numpy()
-    cb = ly.cb.cpu().numpy()
-    new_key = ly.new_key.cpu().numpy()
-    gpu_out = ly.out.cpu().numpy()
+    BH = cfg.B * cfg.H
     threads = oracle.num_threads()
+    cb = ly.cb.cpu().numpy()
+    gpu_out = ly.out.cpu().numpy().reshape(BH, cfg.d_k)
+    flat = lambda t: t.reshape((BH,) + tuple(t.shape[2:]))
+    codes_d, values_d, q_d, key_d = flat(ly.codes), flat(ly.values), flat(ly.q), flat(ly.new_key)
 
-    def once(n):
-        c = codes[:n].copy()
-        c[:, :, cfg.L - 1:cfg.L] = oracle.encode_keys(new_key[:n], cb)
-        lut = oracle.build_lut(q[:n], cb)
-        return oracle.attend_decode(lut[:, :, 0], c, values[:n], scale)
+    def slab(n):
+        """Host copies of the first n (b,h) pairs (b-major: whole batch entries first), as [1, n, ...] arrays
+        with the codebooks of their heads."""
+        idx = np.arange(n)
+        return (codes_d[:n].cpu().numpy()[None], values_d[:n].cpu().numpy()[None], q_d[:n].cpu().numpy()[None],
+                key_d[:n].cpu().numpy()[None], np.ascontiguousarray(cb[idx % cfg.H]))
 
-    # size the sample: time one batch entry, then take as many as fit the budget
+    def once(arrs):
+        codes, values, q, new_key, cbn = arrs
+        c = codes.copy()
+        c[:, :, cfg.L - 1:cfg.L] = oracle.encode_keys(new_key, cbn)
+        lut = oracle.build_lut(q, cbn)
+        return oracle.attend_decode(lut[:, :, 0], c, values, scale)
+
+    def timed(n, budget):
+        arrs = slab(n)
+        reps = 0
+        t0 = time.perf_counter()
+        while True:
+            out = once(arrs)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= budget or reps >= 50:
+                return out, reps, dt
+
+    # size the sample: time one (b,h) pair per thread, then take as many pairs as fit the budget
+    probe = min(BH, threads)
     t0 = time.perf_counter()
-    once(1)
+    once(slab(probe))
     t1 = time.perf_counter() - t0
-    n = int(max(1, min(nb, budget_s / max(t1, 1e-6) / 2)))
-    reps = 0
-    t0 = time.perf_counter()
-    while True:
-        out = once(n)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt >= min(budget_s, 2.0) or reps >= 50:
-            break
-    keys = reps * n * cfg.H * cfg.L
-    err = float(np.max(np.abs(out - gpu_out[:n])))
+    n = int(max(probe, min(BH, probe * budget_s / max(t1, 1e-6) / 4)))
+    out, reps, dt = timed(n, min(budget_s / 2, 2.0))
+    err = float(np.max(np.abs(out[0] - gpu_out[:n])))
+    # one thread: a share of the same sample sized to a few seconds
+    n1 = int(max(1, min(n, n / max(threads, 1) * 2)))
+    oracle.set_num_threads(1)
+    try:
+        _, reps1, dt1 = timed(n1, min(budget_s / 4, 2.0))
+    finally:
+        oracle.set_num_threads(threads)
     return {
-        "value": keys / dt,
+        "value": reps * n * cfg.L / dt,
         "unit": "keys/s",
         "cores": threads,
         "kind": "oracle",
-        "sample": f"layer 0, batch entries 0..{n - 1} of {cfg.B} (all {cfg.H} heads, L={cfg.L}), "
-                  f"{reps} repetitions, fp64, OpenMP over (b,h)",
+        "sample": f"layer 0, the first {n} of {BH} (b,h) pairs (whole slabs, L={cfg.L}), {reps} repetitions, fp64, "
+                  f"OpenMP over (b,h); one thread: the first {n1} pairs, {reps1} repetitions",
+        "single_thread_value": reps1 * n1 * cfg.L / dt1,
         "max_abs_diff_gpu_vs_oracle": err,
     }
 

@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kPfWgThreads, 1) void score_prefill_kernel(const Pr
                 if (a.vec4) {                                                                            \
                     const pf_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};                    \
                     for (uint32_t l = (uint32_t)kfill_ + 4 * ft; l < (uint32_t)a.L; l += 4 * NF)         \
-                        *reinterpret_cast<pf_v4f *>(rowp_ + l) = ninf;                                   \
+                        __builtin_nontemporal_store(ninf, reinterpret_cast<pf_v4f *>(rowp_ + l));        \
                 } else {                                                                                 \
                     for (uint32_t l = (uint32_t)kfill_ + ft; l < (uint32_t)a.L; l += NF)                 \
                         rowp_[l] = -INFINITY;                                                            \
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kPfWgThreads, 1) void score_prefill_kernel(const Pr
             _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
                 o_[j] = ((l0_) + j <= tq_ + (int)off) ? sc_[j][t] : -INFINITY;                           \
             if (a.vec4) {                                                                                \
-                *reinterpret_cast<pf_v4f *>(rowp_ + (uint32_t)(l0_)) = o_;                               \
+                __builtin_nontemporal_store(o_, reinterpret_cast<pf_v4f *>(rowp_ + (uint32_t)(l0_)));    \
             } else {                                                                                     \
                 _Pragma("unroll") for (int j = 0; j < 4; ++j)                                            \
                     if ((l0_) + j < a.L)                                                                 \

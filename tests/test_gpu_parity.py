@@ -180,6 +180,18 @@ def test_build_lut_batched_matrix_core_path(lk, d_k, m, q_dtype, B, T):
     assert_lut_close(got, case["q"], cb, ref)
 
 
+def test_build_lut_tables_beyond_the_cache(lk):
+    """A table set over 256 MiB (here 262 MiB) takes the instance that writes with non-temporal stores;
+    every entry is compared."""
+    cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=4, T=2795, d_k=128, m=16, n_calib=300, q_dtype="float16")
+    case = li.make_case(cfg, seed=2999)
+    cb = case["cb_init"]
+    assert 2 * 3 * 2795 * 16 * 256 * 4 > 256 << 20
+    ref = oracle.build_lut(case["q"], cb)
+    got = lk.lookat_build_lut(dev(case["q"]), dev(cb)).cpu().numpy()
+    assert_lut_close(got, case["q"], cb, ref)
+
+
 # ---------------------------------------------------------------- decode ---------------
 
 def _decode_case(rng, B, H, L, d_k, m, lut_scale=2.0):

@@ -154,11 +154,30 @@ __device__ __forceinline__ double step_sq_dist(UniformWords x, int x0, const flo
 // One 64-key tile of a wavefront: its codes (kc) and first CH value-row groups (v) are in
 // registers or in flight.  Scores one key per lane (key = kb + kofs), updates the running
 // max / sum, and accumulates the weighted value rows.
-template <int DK, int M, int CH, bool FUSED = false, int G = 1>
+//
+// MM (grouped queries, d_k = 128, G >= 4): the weighted value sum of the tile is a dense contraction
+// [G query heads x 64 keys] . [64 keys x 128 coordinates] and runs on the matrix cores
+// (v_mfma_f32_16x16x16_f16, fp32 accumulate) instead of G x 128 multiply-adds per key on the vector ALU:
+//   * A operand = value rows, as loaded: lane (rowin, sub) holds 8 coordinates of the rows 4j + rowin of a
+//     16-key step, j = 0..3.  With the instruction's contraction index k = 4*rowin + j standing for key
+//     4j + rowin, the four halves a lane must supply for coordinate 8*sub + e are element e of its four
+//     loads: two byte permutes per instruction, no data crosses lanes.  Instruction e of a step handles the
+//     coordinates {8*s + e}: row s of its 16 x 16 result is coordinate 8*s + e;
+//   * B operand = weights: column n < G is the weight of query head n rounded to fp16, column G + n the
+//     remainder (p - fp16(p)) * 2^11 rounded to fp16, so that hi + lo * 2^-11 carries 22 bits of p; the
+//     weights go from the scoring lanes (one key per lane, all heads) to the operand layout (one column per
+//     lane, four keys) through 2 KB of LDS per wavefront, rows XOR-swizzled so that neither side conflicts;
+//   * the accumulators (8 instructions x 4 registers) are rescaled only in tiles where a running maximum
+//     moved; hi and lo columns are combined once, after the last tile.
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+constexpr float kLoScale = 2048.f;   // 2^11: lifts the remainder of a weight into fp16's normal range
+
+template <int DK, int M, int CH, bool FUSED = false, int G = 1, bool MM = false>
 __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G> &st, const KeyCodes<M ? M : 4> &kc_in,
                                              v4u (&v)[CH], const float *lut_s, __amdgpu_buffer_rsrc_t rc,
                                              __amdgpu_buffer_rsrc_t rv, int bh, uint32_t kb, uint32_t k1,
-                                             uint32_t kofs, int lane, int m, const double *enc_d = nullptr)
+                                             uint32_t kofs, int lane, int m, const double *enc_d,
+                                             v4f (&accm)[MM ? 8 : 1], uint32_t pstage)
 {
     constexpr int LPR = DK / 8;
     constexpr int NLD = LPR;
@@ -199,6 +218,8 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G
     }
     // one score per query head of the group: the same codes index that head's tables
     float p[G];
+    float corr_n = 1.f;      // MM: the correction of the query head whose column this lane accumulates
+    bool moved = false;      // MM: some head's running maximum changed in this tile (wave-uniform)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         float raw;
@@ -217,10 +238,60 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G
         const float corr = fast_exp2(st.m_run[g] - m_use);
         p[g] = fast_exp2(s - m_use);
         st.z[g] = st.z[g] * corr + p[g];
+        if constexpr (MM) {
+            corr_n = ((lane & (G - 1)) == g) ? corr : corr_n;
+            moved = moved || (m_new != st.m_run[g]);
+        } else {
 #pragma unroll
-        for (int d = 0; d < 8; ++d)
-            st.acc[g][d] *= corr;
+            for (int d = 0; d < 8; ++d)
+                st.acc[g][d] *= corr;
+        }
         st.m_run[g] = m_new;
+    }
+    if constexpr (MM) {
+        static_assert(DK == 128 && CH == 8 && G >= 4 && G <= 8, "matrix-core value sum: d_k = 128, 4 or 8 query heads");
+        if (__builtin_amdgcn_readfirstlane((int)moved)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                accm[e] *= corr_n;
+        }
+        // weights to the staging rows: this lane scored key 16*(sub/4) + 4*(sub%4) + rowin of the tile
+        const uint32_t sub_ = (uint32_t)lane & 15u, rowin_ = (uint32_t)lane >> 4;
+        const uint32_t r_w = (sub_ & ~3u) + rowin_;                 // staging row (step, rowin)
+        const uint32_t w_base = pstage + r_w * 128u + 2u * (sub_ & 3u);
+        const uint32_t w_swz = (r_w >> 1) * 8u;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const _Float16 hi = (_Float16)p[g];
+            const _Float16 lo = (_Float16)((p[g] - (float)hi) * kLoScale);
+            *reinterpret_cast<__attribute__((address_space(3))) _Float16 *>(w_base + (((uint32_t)g * 8u) ^ w_swz)) = hi;
+            *reinterpret_cast<__attribute__((address_space(3))) _Float16 *>(w_base + (((uint32_t)(G + g) * 8u) ^ w_swz)) = lo;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t n_ = sub_, kg_ = rowin_;                    // operand column, contraction group
+#pragma unroll
+        for (int c0 = 0; c0 < NLD; c0 += CH) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                const uint32_t r_r = (uint32_t)(c0 / 4 + tt) * 4u + kg_;
+                const v4h bw = *reinterpret_cast<const __attribute__((address_space(3))) v4h *>(
+                    pstage + r_r * 128u + ((n_ * 8u) ^ ((r_r >> 1) * 8u)));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                    v2u aw;
+                    aw.x = __builtin_amdgcn_perm(v[4 * tt + 1][e >> 1], v[4 * tt + 0][e >> 1], sel);
+                    aw.y = __builtin_amdgcn_perm(v[4 * tt + 3][e >> 1], v[4 * tt + 2][e >> 1], sel);
+                    accm[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(v4h, aw), bw, accm[e], 0, 0, 0);
+                }
+            }
+            if (c0 + CH < NLD)
+                load_rows<DK, CH>(v, rv, kb, c0 + CH, lane);   // next row groups of this tile
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_wave_barrier();   // the next tile's weights overwrite the staging rows
+        return;
     }
 #pragma unroll
     for (int c0 = 0; c0 < NLD; c0 += CH) {
@@ -363,6 +434,7 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     constexpr int NLD = kTile / RPL;       // wave-wide loads per tile (= LPR)
     constexpr int CH = NLD < 8 ? NLD : 8;  // loads kept in flight together
     constexpr int NT = WAVES * kWave;
+    constexpr bool MM = (G >= 4 && DK == 128 && M != 0);   // weighted value sum on the matrix cores
 
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                                   // [G][m][256]
@@ -471,35 +543,69 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     // are requested only if they exist (a load past the range would return zero but still
     // occupy the address pipeline), and a tile's registers are dead at the loop back-edge.
     SoftmaxState<G> st;
+    // Matrix-core value sum (see consume_tile): accumulators, and the wavefront's weight staging rows, which
+    // occupy its own slice of the reduction buffer (unused until the epilogue; 2 KB of its G x (DK + 2) floats).
+    v4f accm[MM ? 8 : 1];
+#pragma unroll
+    for (int e = 0; e < (MM ? 8 : 1); ++e)
+        accm[e] = v4f{0.f, 0.f, 0.f, 0.f};
+    uint32_t pstage = 0;
+    if constexpr (MM) {
+        static_assert(G * (DK + 2) * sizeof(float) >= 2048, "the staging rows fit the wavefront's reduction slice");
+        pstage = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)(red_s + wave * G * (DK + 2));
+        // columns no query head owns (G = 4: 8..15) must read as zero in every tile
+        *reinterpret_cast<__attribute__((address_space(3))) v4f *>(pstage + (uint32_t)lane * 32u) = v4f{0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<__attribute__((address_space(3))) v4f *>(pstage + (uint32_t)lane * 32u + 16u) = v4f{0.f, 0.f, 0.f, 0.f};
+    }
     if (kb < k1) {
-        consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+        consume_tile<DK, M, CH, FUSED, G, MM>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d, accm, pstage);
 #pragma unroll
         for (int t = 1; t < PF; ++t) {   // the other tiles requested at the start
             kb += NT;
             if (kb < k1)
-                consume_tile<DK, M, CH, FUSED, G>(a, st, kcs[t], vs[t], lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+                consume_tile<DK, M, CH, FUSED, G, MM>(a, st, kcs[t], vs[t], lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d, accm,
+                                                      pstage);
         }
         for (kb += NT; kb < k1; kb += NT) {
             if constexpr (M != 0)
                 kc.load(rc, (kb + kofs) * M);
             __builtin_amdgcn_sched_barrier(0);   // request order = need order: codes before value rows
             load_rows<DK, CH>(v, rv, kb, 0, lane);
-            consume_tile<DK, M, CH, FUSED, G>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d);
+            consume_tile<DK, M, CH, FUSED, G, MM>(a, st, kc, v, lut_s, rc, rv, bh, kb, k1, kofs, lane, m, enc_d, accm, pstage);
         }
     }
 
     // ---- fold the rows of the wave, then the waves of the workgroup ----
+    if constexpr (MM) {
+        // lane (q, n): accm[e][r] = coordinate 8*(4q + r) + e of column n; columns n < G hold the fp16 part of
+        // the weights, columns G + n the scaled remainder: combine, and lanes n < G hand over head n's sum
+        const int n = lane & 15, q = lane >> 4;
+        float *mine_n = red_s + (wave * G + (n & (G - 1))) * (DK + 2);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float lo = dpp_mov<0x100 + G>(accm[e][r], accm[e][r]);   // row_shl:G -- lane n + G of the row
+                const float o = fmaf(lo, 1.f / kLoScale, accm[e][r]);
+                if (n < G)
+                    mine_n[8 * (4 * q + r) + e] = o;
+            }
+    }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int d = 0; d < 8; ++d)
-            st.acc[g][d] = sum_over_lane_classes<LPR>(st.acc[g][d]);
-        st.z[g] = wave_sum(st.z[g]);
-        float *mine = red_s + (wave * G + g) * (DK + 2);
-        if (lane < LPR) {
+        if constexpr (!MM) {
 #pragma unroll
             for (int d = 0; d < 8; ++d)
-                mine[sub * 8 + d] = st.acc[g][d];
+                st.acc[g][d] = sum_over_lane_classes<LPR>(st.acc[g][d]);
+        }
+        st.z[g] = wave_sum(st.z[g]);
+        float *mine = red_s + (wave * G + g) * (DK + 2);
+        if constexpr (!MM) {
+            if (lane < LPR) {
+#pragma unroll
+                for (int d = 0; d < 8; ++d)
+                    mine[sub * 8 + d] = st.acc[g][d];
+            }
         }
         if (lane == 0) {
             mine[DK] = st.m_run[g];

@@ -692,6 +692,26 @@ def test_attend_decode_gqa_parity(lk, d_k, m, g, L, splits):
     assert_out_close(out.cpu().numpy(), out_ref, "attend_decode_gqa", s_ref, scale)
 
 
+@pytest.mark.parametrize("g", [4, 8])
+@pytest.mark.parametrize("L,splits,lut_scale", [(8229, 0, 0.05), (16421, 1, 0.05), (16421, 0, 3.0), (9000, 2, 40.0)])
+def test_attend_decode_gqa_matrix_core_sum_long_context(lk, g, L, splits, lut_scale):
+    """d_k = 128 with 4 or 8 query heads per key/value head takes the weighted value sum on the matrix cores,
+    the weights split into two fp16 halves.  Long contexts with a near-flat softmax (every weight about 1/L:
+    the split's error would add up over 16 K keys), a peaked one, and one so peaked that most weights are
+    below fp16's range: outputs to the arithmetic bar of tests/bars.py, scores to theirs."""
+    B, H, d_k, m = 1, 2, 128, 8
+    rng = np.random.default_rng(9200 + g + L + int(lut_scale * 10))
+    lut = (rng.standard_normal((B, H * g, m, 256)) * lut_scale).astype(np.float32)
+    codes = rng.integers(0, 256, size=(B, H, L, m), dtype=np.uint8)
+    v = rng.standard_normal((B, H, L, d_k)).astype(np.float16)
+    scale = 1.0 / math.sqrt(d_k)
+    out_ref, s_ref = oracle.attend_decode_gqa(lut, codes, v, scale, want_scores=True)
+    s_gpu = torch.empty((B, H * g, L), dtype=torch.float32, device="cuda")
+    out = lk.lookat_attend_decode_gqa(dev(lut), dev(codes), dev(v), scale, num_splits=splits, scores_out=s_gpu)
+    assert_scores_close(s_gpu.cpu().numpy(), lut, np.repeat(codes, g, axis=1), s_ref)
+    assert_out_close(out.cpu().numpy(), out_ref, "attend_decode_gqa, matrix-core value sum, long context", s_ref, scale)
+
+
 def test_attend_decode_gqa_equals_per_head_calls(lk):
     """The grouped kernel against lookat_attend_decode on caches repeated per query head, and
     on views of a longer cache."""

@@ -84,6 +84,20 @@ int lookat_probe_attend_decode_ticket(const lookat_shape *shape, int64_t L,
                                       int32_t *pieces_per_unit,
                                       void *stream);
 
+/*
+ * lookat_score_prefill forced onto its lookup-and-sum kernel (per-query tables built and gathered in LDS,
+ * paper Sec. 3.5 as written), whatever the shape: lookat_score_prefill itself scores blocks of 32 or more
+ * fp16 queries as a dense product against the keys' centroids on the matrix cores.  Same arguments, results
+ * and error behaviour as lookat_score_prefill; exists so that both kernels can be timed and checked against
+ * the oracle on the same inputs.
+ */
+int lookat_probe_score_prefill_lookup(const lookat_shape *shape, int32_t T, int64_t L,
+                                      const void *q, lookat_dtype q_dtype,
+                                      const float *codebooks,
+                                      const uint8_t *codes, int64_t code_stride_bh,
+                                      float *scores,
+                                      void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -74,6 +74,8 @@ def load_library():
         lib.lookat_decode_step_gqa.restype = ctypes.c_int
         lib.lookat_score_prefill.argtypes = [sp, i32, i64, vp, ctypes.c_int, vp, vp, i64, vp, vp]
         lib.lookat_score_prefill.restype = ctypes.c_int
+        lib.lookat_probe_score_prefill_lookup.argtypes = lib.lookat_score_prefill.argtypes
+        lib.lookat_probe_score_prefill_lookup.restype = ctypes.c_int
         lib.lookat_kmeans_step.argtypes = [sp, i64, vp, vp, vp, vp, vp]
         lib.lookat_kmeans_step.restype = ctypes.c_int
         lib.lookat_probe_stream_read.argtypes = [vp, sz, vp, vp]
@@ -414,7 +416,7 @@ def _decode_step(q, k_new, codebooks, codes, values, scale, out, num_splits, wor
 
 
 def lookat_score_prefill(q: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
-                         scores_out: torch.Tensor | None = None) -> torch.Tensor:
+                         scores_out: torch.Tensor | None = None, _entry: str = "lookat_score_prefill") -> torch.Tensor:
     """q [B,H,T,d_k] fp16|fp32, codes [B,H,L,m] u8 (L >= T) -> causal scores [B,H,T,L] fp32
     (-inf where key l is later than query t's position t + L - T)."""
     lib = load_library()
@@ -434,9 +436,15 @@ def lookat_score_prefill(q: torch.Tensor, codebooks: torch.Tensor, codes: torch.
     if scores_out.dtype != torch.float32 or scores_out.numel() != B * H * T * L or not scores_out.is_contiguous():
         raise ValueError("scores_out must be contiguous fp32 [B,H,T,L]")
     shape = _Shape(B, H, d_k, m, K)
-    _check(lib.lookat_score_prefill(ctypes.byref(shape), T, L, q.data_ptr(), _dtype_tag(q), cb.data_ptr(),
-                                    codes.data_ptr(), cs, scores_out.data_ptr(), _stream(q)))
+    _check(getattr(lib, _entry)(ctypes.byref(shape), T, L, q.data_ptr(), _dtype_tag(q), cb.data_ptr(),
+                                codes.data_ptr(), cs, scores_out.data_ptr(), _stream(q)))
     return scores_out
+
+
+def lookat_probe_score_prefill_lookup(q: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
+                                      scores_out: torch.Tensor | None = None) -> torch.Tensor:
+    """lookat_score_prefill forced onto its lookup-and-sum kernel (measurement aid)."""
+    return lookat_score_prefill(q, codebooks, codes, scores_out, _entry="lookat_probe_score_prefill_lookup")
 
 
 def lookat_kmeans_step(calib: torch.Tensor, codebooks: torch.Tensor, codebooks_out: torch.Tensor | None = None,

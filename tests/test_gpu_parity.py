@@ -419,42 +419,81 @@ def _prefill_bars(got, ref, q, cb, codes, lut_ref, label):
         ent = np.abs(lut_ref[:, :, :, i, :].astype(np.float64))                      # [B,H,T,K]
         narrow += ent[bidx, hidx, :, codes[:, :, :, i].astype(np.int64)].transpose(0, 1, 3, 2)   # [B,H,T,L]
     miss = int(np.count_nonzero(err[vis] > REL * np.maximum(narrow[vis], 1e-6)))
-    _PREFILL_NARROW["entries"] += int(vis.sum())
-    _PREFILL_NARROW["missed"] += miss
+    tally = _PREFILL_NARROW.setdefault(label, {"entries": 0, "missed": 0})
+    tally["entries"] += int(vis.sum())
+    tally["missed"] += miss
     record(label + ": worst |err| / (1e-4 * sum_i |LUT_i[c_i]|)",
            float(np.max(err[vis] / (REL * np.maximum(narrow[vis], 1e-6)))))
-    record(label + ": entries checked", _PREFILL_NARROW["entries"])
-    record(label + ": entries outside the table-entry bar", _PREFILL_NARROW["missed"])
+    record(label + ": entries checked", tally["entries"])
+    record(label + ": entries outside the table-entry bar", tally["missed"])
     # the wider form may be needed only by a vanishing share of the entries
     assert miss <= 1e-5 * vis.sum() + 2, f"{miss} of {vis.sum()} entries miss the table-entry bar"
 
 
-_PREFILL_NARROW = {"entries": 0, "missed": 0}
+_PREFILL_NARROW = {}   # label -> entries checked / entries outside the table-entry bar
+
+# lookat_score_prefill has two kernels: blocks of 32 or more fp16 queries are scored as a dense product
+# against the keys' centroids on the matrix cores, everything else by lookup-and-sum in LDS.  "library"
+# takes the library's choice, "lookup" forces the lookup-and-sum kernel through its measurement-aid entry
+# point, so that it stays covered on the shapes the library no longer routes to it.
+_PREFILL_ENTRIES = {"library": ("lookat_score_prefill", "score_prefill"),
+                    "lookup": ("lookat_probe_score_prefill_lookup", "score_prefill, lookup-and-sum kernel forced")}
 
 
-def _prefill_check(lk, case, cb, codes):
+def _prefill_check(lk, case, cb, codes, path="library"):
     q = case["q"]
+    entry, label = _PREFILL_ENTRIES[path]
     lut_ref = oracle.build_lut(q, cb)
     ref = oracle.score_prefill(lut_ref, codes)
-    got = lk.lookat_score_prefill(dev(q), dev(cb), dev(codes)).cpu().numpy()
+    got = getattr(lk, entry)(dev(q), dev(cb), dev(codes)).cpu().numpy()
     assert got.shape == ref.shape
-    _prefill_bars(got, ref, q, cb, codes, lut_ref, "score_prefill")
+    _prefill_bars(got, ref, q, cb, codes, lut_ref, label)
 
 
 @pytest.mark.parametrize("d_k,m", [(128, 16), (128, 8), (64, 4), (64, 2), (64, 16)])
-@pytest.mark.parametrize("q_dtype", ["float16", "float32"])
+@pytest.mark.parametrize("q_dtype,path", [("float16", "library"), ("float16", "lookup"), ("float32", "library")])
 @pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135), (64, 0), (40, 24), (300, 1300),
-                                     (40, 2101), (100, 4200)])
-def test_score_prefill_parity(lk, d_k, m, q_dtype, T, extra):
-    """Ragged query tiles (T not a multiple of 4), one workgroup per (b,h) and several, queries that are
-    the tail of a longer cache (extra > 0), a single query, contexts beyond the 2048 keys whose codes
-    the scoring threads keep in registers (one and two further rounds of keys, L odd: scalar stores)."""
+                                     (40, 2101), (100, 4200), (32, 0), (31, 97), (129, 3), (96, 160)])
+def test_score_prefill_parity(lk, d_k, m, q_dtype, path, T, extra):
+    """Ragged query tiles (T not a multiple of 4 or of 32), one workgroup per (b,h) and several, queries that
+    are the tail of a longer cache (extra > 0), a single query, contexts beyond the 2048 keys whose codes
+    the lookup kernel's scoring threads keep in registers (one and two further rounds of keys), L odd (scalar
+    stores), key panels that end inside a 128-key panel or exactly on one, T on either side of the 32 queries
+    from which fp16 blocks go to the matrix cores."""
     L = T + extra
     cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)
     case = li.make_case(cfg, seed=5000 + d_k + m + T)
     cb = case["cb_init"]
     codes = oracle.encode_keys(case["keys"], cb)
-    _prefill_check(lk, case, cb, codes)
+    _prefill_check(lk, case, cb, codes, path)
+
+
+def test_score_prefill_matrix_core_kernel_wide_range_codebook(lk):
+    """The matrix-core kernel scales each wavefront's centroids by a power of two and splits them into two
+    fp16 terms, which keeps 22 bits of every entry down to 2^-27 of the wavefront's largest: a codebook whose
+    subspaces sit at scales from 1e-3 to 1e3 (every wavefront meets all of them), with queries that weight the
+    small subspaces up so that all of them matter in the sum, must still meet the bar relative to the summed
+    products."""
+    rng = np.random.default_rng(5200)
+    B, H, T, L, d_k, m = 1, 2, 160, 300, 128, 16
+    d_sub = d_k // m
+    sub_scale = 10.0 ** rng.uniform(-3, 3, size=(H, m, 1, 1))
+    cb = (rng.standard_normal((H, m, 256, d_sub)) * sub_scale).astype(np.float32)
+    q = (rng.standard_normal((B, H, T, m, d_sub)) / sub_scale[None, :, :, 0, :].reshape(1, H, 1, m, 1)).reshape(B, H, T, d_k)
+    q = q.astype(np.float16)
+    codes = rng.integers(0, 256, size=(B, H, L, m), dtype=np.uint8)
+    lut_ref = oracle.build_lut(q, cb)
+    ref = oracle.score_prefill(lut_ref, codes)
+    got = lk.lookat_score_prefill(dev(q), dev(cb), dev(codes)).cpu().numpy()
+    vis = np.isfinite(ref)
+    assert np.array_equal(np.isneginf(got), ~vis)
+    qa = np.abs(q.astype(np.float64)).reshape(B, H, T, m, d_sub)
+    hidx = np.arange(H)[None, :, None]
+    picked = np.stack([np.abs(cb.astype(np.float64))[hidx, i, codes[:, :, :, i].astype(np.int64)] for i in range(m)], axis=3)
+    mag = np.einsum("bhtid,bhlid->bhtl", qa, picked)
+    err = np.abs(np.where(vis, got, 0.0).astype(np.float64) - np.where(vis, ref, 0.0).astype(np.float64))
+    record("score_prefill, wide-range codebook: worst |err| / sum_j |q_j c_j|", float(np.max(err[vis] / np.maximum(mag[vis], 1e-30))))
+    assert np.all(err[vis] <= REL * np.maximum(mag[vis], 1e-6)), f"max err {err[vis].max()}"
 
 
 def test_score_prefill_single_head_and_padded_cache(lk):

@@ -15,16 +15,16 @@
 //     strip of all T score rows: -inf for the queries that cannot see the panel, scores for the others.
 //     Every workgroup of a launch writes the same number of bytes; the matrix work differs (early panels
 //     are seen by more queries) and is a small part of the time.
-//   * wavefront w holds keys 32w .. 32w+31 of the panel as the B operand of v_mfma_f32_32x32x8_f16: per
-//     8-coordinate step, lane (key n, half g) fetches coordinates 8s+4g .. +3 of the centroid its key's code
-//     selects (16 bytes of an fp32 codebook row), scales by a power of two chosen per wavefront so that the
+//   * wavefront w holds keys 32w .. 32w+31 of the panel as the B operand of v_mfma_f32_32x32x16_f16: per
+//     16-coordinate step, lane (key n, half g) fetches coordinates 16s+8g .. +7 of the centroids its key's codes
+//     select (two 16-byte pieces of fp32 codebook rows), scales by a power of two chosen per wavefront so that the
 //     largest fetched entry sits near 2^13, and splits the result into two fp16 terms, hi = fp16(w) and
 //     lo = fp16((w - hi) * 2^11): hi + lo * 2^-11 carries 22 bits of w, and fp16 x fp16 products are exact in
 //     the fp32 accumulators.  Two accumulator sets (hi and lo terms) are combined when a tile is finished.
 //   * queries are taken in tiles of 32 (the A operand): a tile (8 KB of fp16, contiguous in memory) is
-//     staged in LDS by the whole workgroup, rows padded by 8 bytes so that the operand reads of a
-//     half-wavefront fall on distinct banks; the next tile is requested before the current one is multiplied
-//     and written to the other buffer afterwards.
+//     staged in LDS by the whole workgroup, rows padded by 16 bytes so that the 16-byte operand reads of
+//     sixteen lanes fall on distinct banks; the tile after the next is requested while the current one is
+//     multiplied and written to the other buffer a step later.
 //   * a tile's 32 x 128 results cross LDS once more so that they leave as 16-byte non-temporal stores, 512
 //     contiguous bytes of a score row per half-wavefront (stored straight from the accumulators a store
 //     instruction would write 4 bytes per lane).  The causal mask is applied on the way into LDS.
@@ -40,7 +40,7 @@
 
 namespace lookat {
 
-typedef _Float16 pd_v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 pd_v8h __attribute__((ext_vector_type(8)));
 typedef float pd_v4f __attribute__((ext_vector_type(4)));
 typedef float pd_v16f __attribute__((ext_vector_type(16)));
 typedef unsigned int pd_v2u __attribute__((ext_vector_type(2)));
@@ -71,8 +71,8 @@ template <int DK, int M>
 __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(const PrefillDenseArgs a)
 {
     constexpr int DSUB = DK / M;
-    constexpr int KS = DK / 8;                       // 8-coordinate steps of the contraction
-    constexpr int QROW = DK * 2 + 8;                 // bytes per staged query row
+    constexpr int KS = DK / 16;                      // 16-coordinate steps of the contraction
+    constexpr int QROW = DK * 2 + 16;                // bytes per staged query row
     static_assert(DSUB % 4 == 0, "a 4-coordinate operand group lies inside one subspace");
     __shared__ __align__(16) unsigned char q_s[2][kPdTQ * QROW];
     __shared__ __align__(16) float stage_s[2][kPdTQ * kPdStageStride];
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int n = lane & 31;          // key column (B operand, result), query row (A operand)
-    const int g = lane >> 5;          // which half of an 8-coordinate step
+    const int g = lane >> 5;          // which half of a 16-coordinate step
     const int64_t off = a.L - a.T;    // query t sits at position t + off
     const int l0 = panel * kPdPanel;
     const __half *qg = a.q + (int64_t)bh * a.T * DK;
@@ -123,14 +123,13 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
         const int c_ = tid + k * kPdThreads;                                                              \
         if (QCHUNKS % kPdThreads == 0 || c_ < QCHUNKS) {                                                  \
             unsigned char *dst_ = q_s[buf_] + (c_ / (DK / 8)) * QROW + (c_ % (DK / 8)) * 16;              \
-            *reinterpret_cast<pd_v2u *>(dst_) = pd_v2u{qreg[k].x, qreg[k].y};                             \
-            *reinterpret_cast<pd_v2u *>(dst_ + 8) = pd_v2u{qreg[k].z, qreg[k].w};                         \
+            *reinterpret_cast<pd_v4u *>(dst_) = qreg[k];                                                  \
         }                                                                                                 \
     }
     LOOKAT_PD_FETCH_Q(tile_first)
 
     // ---- the stationary operand: centroids of this wavefront's 32 keys, by code ----
-    pd_v4h b_hi[KS], b_lo[KS];
+    pd_v8h b_hi[KS], b_lo[KS];
     float inv_scale;
     {
         const int64_t key = (int64_t)l0 + wave * 32 + n;
@@ -153,18 +152,20 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
             cw[3] = t.w;
         }
         const float *cb_h = a.codebooks + (int64_t)h * M * kCentroids * DSUB;
-        pd_v4f raw[KS];
+        pd_v4f raw[KS][2];
         float cmax = 0.f;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const int dim0 = 8 * s + 4 * g;
-            const int i = dim0 / DSUB;                                // the subspace of this coordinate group
-            const uint32_t code = (cw[i / 4] >> (8 * (i % 4))) & 0xffu;
-            raw[s] = *reinterpret_cast<const pd_v4f *>(cb_h + ((int64_t)i * kCentroids + code) * DSUB + dim0 % DSUB);
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                cmax = fmaxf(cmax, fabsf(raw[s][e]));
-        }
+            for (int u = 0; u < 2; ++u) {
+                const int dim0 = 16 * s + 8 * g + 4 * u;                  // four coordinates inside one subspace
+                const int i = dim0 / DSUB;
+                const uint32_t code = (cw[i / 4] >> (8 * (i % 4))) & 0xffu;
+                raw[s][u] = *reinterpret_cast<const pd_v4f *>(cb_h + ((int64_t)i * kCentroids + code) * DSUB + dim0 % DSUB);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    cmax = fmaxf(cmax, fabsf(raw[s][u][e]));
+            }
         cmax = wave_max(cmax);
         int ex = (int)((__float_as_uint(cmax) >> 23) & 0xffu) - 127;   // floor(log2(cmax)) for normal numbers
         if (cmax == 0.f)
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float w = scale * raw[s][e];                    // exact: a power of two
+            for (int e = 0; e < 8; ++e) {
+                const float w = scale * raw[s][e / 4][e % 4];         // exact: a power of two
                 const _Float16 wh = (_Float16)w;
                 b_hi[s][e] = wh;
                 b_lo[s][e] = (_Float16)((w - (float)wh) * kPdLoScale);   // exact difference and scaling, one rounding
@@ -215,12 +216,12 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
             acc_h[r] = 0.f;
             acc_l[r] = 0.f;
         }
-        const unsigned char *qrow = q_s[buf] + n * QROW + g * 8;
+        const unsigned char *qrow = q_s[buf] + n * QROW + g * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const pd_v4h av = *reinterpret_cast<const pd_v4h *>(qrow + s * 16);
-            acc_h = __builtin_amdgcn_mfma_f32_32x32x8f16(av, b_hi[s], acc_h, 0, 0, 0);
-            acc_l = __builtin_amdgcn_mfma_f32_32x32x8f16(av, b_lo[s], acc_l, 0, 0, 0);
+            const pd_v8h av = *reinterpret_cast<const pd_v8h *>(qrow + s * 32);
+            acc_h = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b_hi[s], acc_h, 0, 0, 0);
+            acc_l = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b_lo[s], acc_l, 0, 0, 0);
         }
         // result register r of lane (n, g): query row 8*(r/4) + 4*g + r%4 of the tile, key column n
         const int t0 = tile * kPdTQ;

@@ -471,11 +471,11 @@ static int dispatch_prefill(const lookat_shape *s, const PrefillArgs &a, hipStre
 }
 
 // prefill_dense.hip: the same scores as a dense contraction against the keys' centroids on the matrix cores
-// (fp16 queries, d_k in {64, 128}, m in {2, 4, 8, 16}); returns false when it does not take the shape.
-bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q, const float *codebooks,
+// (d_k in {64, 128}, m in {2, 4, 8, 16}); returns false when it does not take the shape.
+bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q, bool q_fp32, const float *codebooks,
                           const uint8_t *codes, int64_t code_stride_bh, float *scores, hipStream_t st);
 
-// From this many queries per (b,h) on, blocks of fp16 queries are scored on the matrix cores: a 32-query
+// From this many queries per (b,h) on, blocks of queries are scored on the matrix cores: a 32-query
 // operand tile is then full, and the kernel is bound by the scores it writes; below it the
 // lookup-and-sum kernel, whose tiles hold four queries, wastes less.
 constexpr int kPfDenseMinT = 32;
@@ -518,8 +518,8 @@ static int score_prefill_impl(const lookat_shape *shape, int32_t T, int64_t L, c
     a.groups = 0;
     a.vec4 = (L % 4 == 0) && aligned16(scores);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (allow_dense && q_dtype == LOOKAT_F16 && T >= kPfDenseMinT &&
-        launch_prefill_dense(shape, T, L, q, codebooks, codes, code_stride_bh, scores, st))
+    if (allow_dense && T >= kPfDenseMinT &&
+        launch_prefill_dense(shape, T, L, q, q_dtype == LOOKAT_F32, codebooks, codes, code_stride_bh, scores, st))
         return check_launch("lookat_score_prefill");
     return (q_dtype == LOOKAT_F16) ? dispatch_prefill<__half>(shape, a, st) : dispatch_prefill<float>(shape, a, st);
 }

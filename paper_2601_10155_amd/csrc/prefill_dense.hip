@@ -34,13 +34,17 @@
 // Arithmetic: products exact, fp32 accumulation in the matrix unit's order over all d_k coordinates (not
 // per subspace first); |error| <= (d_k * 2^-24 + 2^-22) * sum_j |q_j| |c_j|, inside the bar of 1e-4 of the
 // same sum that the lookup-and-sum kernel is held to.
-// Used for fp16 queries, T >= 32, d_k in {64, 128}, d_sub a multiple of 4; everything else takes the
-// lookup-and-sum kernel.
+// fp32 queries are split like the centroids (per query row, on their way into LDS); the products of the two
+// small terms (2^-22 of a product) are dropped.
+// Used for T >= 32, d_k in {64, 128}, d_sub a multiple of 4; everything else takes the lookup-and-sum kernel.
+#include <type_traits>
+
 #include "common.h"
 
 namespace lookat {
 
 typedef _Float16 pd_v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 pd_v4h16 __attribute__((ext_vector_type(4)));
 typedef float pd_v4f __attribute__((ext_vector_type(4)));
 typedef float pd_v16f __attribute__((ext_vector_type(16)));
 typedef unsigned int pd_v2u __attribute__((ext_vector_type(2)));
@@ -54,7 +58,7 @@ constexpr int kPdStageStride = kPdPanel + 4;   // floats per staged score row (p
 constexpr float kPdLoScale = 2048.f;
 
 struct PrefillDenseArgs {
-    const __half *q;          // [BH, T, d_k]
+    const void *q;            // [BH, T, d_k] fp16 or fp32
     const float *codebooks;   // [H, m, 256, d_sub]
     const uint8_t *codes;     // (bh, l, i) at bh*code_stride + l*m + i
     float *scores;            // [BH, T, L]
@@ -67,14 +71,37 @@ struct PrefillDenseArgs {
     int vec4;                 // L % 4 == 0 and scores 16-byte aligned
 };
 
-template <int DK, int M>
+// Largest |x| over the aligned group of NL consecutive lanes (NL = 16 or 32); every lane gets the result.
+template <int NL>
+__device__ __forceinline__ float pd_group_max(float v)
+{
+    v = fmaxf(v, dpp_mov<0xB1>(v, v));    // lane ^ 1
+    v = fmaxf(v, dpp_mov<0x4E>(v, v));    // lane ^ 2
+    v = fmaxf(v, dpp_mov<0x141>(v, v));   // the other quad of each 8
+    v = fmaxf(v, dpp_mov<0x140>(v, v));   // the other 8 of each 16
+    if constexpr (NL == 32) {
+        float x, y;
+        lanes_xor16(v, x, y);
+        v = fmaxf(x, y);
+    }
+    return v;
+}
+
+// QT = __half: the queries are the A operand as they are.  QT = float: each query row is scaled by its own
+// power of two (largest entry near 2^13) and split into two fp16 terms like the centroids, on its way into LDS;
+// three products per step (hi.hi; hi.lo and lo.hi share the 2^-11 accumulator; lo.lo, 2^-22 of the product,
+// is dropped) and the row's scale is undone when the tile is finished.
+template <typename QT, int DK, int M>
 __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(const PrefillDenseArgs a)
 {
+    constexpr bool Q32 = std::is_same<QT, float>::value;
     constexpr int DSUB = DK / M;
     constexpr int KS = DK / 16;                      // 16-coordinate steps of the contraction
-    constexpr int QROW = DK * 2 + 16;                // bytes per staged query row
+    constexpr int QROW = DK * 2 + 16;                // bytes per staged query row (fp16 terms)
+    constexpr int QE = 16 / (int)sizeof(QT);         // query elements per 16-byte chunk
     static_assert(DSUB % 4 == 0, "a 4-coordinate operand group lies inside one subspace");
-    __shared__ __align__(16) unsigned char q_s[2][kPdTQ * QROW];
+    __shared__ __align__(16) unsigned char q_s[2][Q32 ? 2 : 1][kPdTQ * QROW];     // [buffer][hi, lo][row]
+    __shared__ float qinv_s[2][kPdTQ];                                             // fp32 queries: 1 / row scale
     __shared__ __align__(16) float stage_s[2][kPdTQ * kPdStageStride];
 
     // workgroup ids go round-robin to the 8 dies; all panels of a (b,h) stay on one die (its queries are
@@ -96,7 +123,7 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
     const int g = lane >> 5;          // which half of a 16-coordinate step
     const int64_t off = a.L - a.T;    // query t sits at position t + off
     const int l0 = panel * kPdPanel;
-    const __half *qg = a.q + (int64_t)bh * a.T * DK;
+    const QT *qg = static_cast<const QT *>(a.q) + (int64_t)bh * a.T * DK;
     float *scores_bh = a.scores + (int64_t)bh * a.T * a.L;
     const int ntiles = (a.T + kPdTQ - 1) / kPdTQ;
     // first query that sees the panel's first key, and its tile
@@ -104,26 +131,50 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
     const int tile_first = (int)(t_first / kPdTQ);
 
     // ---- the next step's query tile: 16-byte chunks dealt to the threads, requested ahead ----
-    constexpr int QCHUNKS = kPdTQ * DK * 2 / 16;                        // chunks of a tile
+    constexpr int QCHUNKS = kPdTQ * DK * (int)sizeof(QT) / 16;          // chunks of a tile
+    constexpr int CPR = DK / QE;                                        // chunks per query row
     constexpr int NQ = (QCHUNKS + kPdThreads - 1) / kPdThreads;         // chunks per thread
+    static_assert(!Q32 || (QCHUNKS % kPdThreads == 0 && (CPR == 16 || CPR == 32)),
+                  "fp32 queries: a row's chunks sit in 16 or 32 consecutive lanes (the row maximum is a lane-group maximum)");
     pd_v4u qreg[NQ];
 #define LOOKAT_PD_FETCH_Q(tile_)                                                                          \
     _Pragma("unroll") for (int k = 0; k < NQ; ++k)                                                        \
     {                                                                                                     \
         const int c_ = tid + k * kPdThreads;              /* 16-byte chunk of the tile */                 \
-        const int row_ = c_ / (DK / 8);                                                                   \
+        const int row_ = c_ / CPR;                                                                        \
         const int64_t t_ = (int64_t)(tile_) * kPdTQ + row_;                                               \
         qreg[k] = ((tile_) < ntiles && c_ < QCHUNKS && t_ < a.T)                                          \
-                      ? *reinterpret_cast<const pd_v4u *>(qg + t_ * DK + (c_ % (DK / 8)) * 8)             \
+                      ? *reinterpret_cast<const pd_v4u *>(qg + t_ * DK + (c_ % CPR) * QE)                 \
                       : pd_v4u{0u, 0u, 0u, 0u};                                                           \
     }
 #define LOOKAT_PD_PUT_Q(buf_)                                                                             \
     _Pragma("unroll") for (int k = 0; k < NQ; ++k)                                                        \
     {                                                                                                     \
         const int c_ = tid + k * kPdThreads;                                                              \
-        if (QCHUNKS % kPdThreads == 0 || c_ < QCHUNKS) {                                                  \
-            unsigned char *dst_ = q_s[buf_] + (c_ / (DK / 8)) * QROW + (c_ % (DK / 8)) * 16;              \
-            *reinterpret_cast<pd_v4u *>(dst_) = qreg[k];                                                  \
+        if constexpr (!Q32) {                                                                             \
+            if (QCHUNKS % kPdThreads == 0 || c_ < QCHUNKS)                                                \
+                *reinterpret_cast<pd_v4u *>(q_s[buf_][0] + (c_ / CPR) * QROW + (c_ % CPR) * 16) = qreg[k]; \
+        } else {                                                                                          \
+            float x_[4];                                                                                  \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) x_[e] = __uint_as_float(qreg[k][e]);           \
+            const float rmax_ = pd_group_max<CPR>(fmaxf(fmaxf(fabsf(x_[0]), fabsf(x_[1])), fmaxf(fabsf(x_[2]), fabsf(x_[3])))); \
+            int ex_ = (int)((__float_as_uint(rmax_) >> 23) & 0xffu) - 127;                                \
+            if (rmax_ == 0.f)                                                                             \
+                ex_ = 0;                                                                                  \
+            int se_ = 13 - ex_;                                                                           \
+            se_ = se_ > 100 ? 100 : (se_ < -100 ? -100 : se_);                                            \
+            const float qs_ = __uint_as_float((uint32_t)(se_ + 127) << 23);                               \
+            pd_v4h16 hi_, lo_;                                                                            \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e)                                                 \
+            {                                                                                             \
+                const float w_ = qs_ * x_[e];                                                             \
+                hi_[e] = (_Float16)w_;                                                                    \
+                lo_[e] = (_Float16)((w_ - (float)hi_[e]) * kPdLoScale);                                   \
+            }                                                                                             \
+            *reinterpret_cast<pd_v4h16 *>(q_s[buf_][0] + (c_ / CPR) * QROW + (c_ % CPR) * 8) = hi_;       \
+            *reinterpret_cast<pd_v4h16 *>(q_s[buf_][Q32 ? 1 : 0] + (c_ / CPR) * QROW + (c_ % CPR) * 8) = lo_; \
+            if (c_ % CPR == 0)                                                                            \
+                qinv_s[buf_][c_ / CPR] = __uint_as_float((uint32_t)(127 - se_) << 23);                    \
         }                                                                                                 \
     }
     LOOKAT_PD_FETCH_Q(tile_first)
@@ -216,12 +267,16 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
             acc_h[r] = 0.f;
             acc_l[r] = 0.f;
         }
-        const unsigned char *qrow = q_s[buf] + n * QROW + g * 16;
+        const unsigned char *qrow = q_s[buf][0] + n * QROW + g * 16;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const pd_v8h av = *reinterpret_cast<const pd_v8h *>(qrow + s * 32);
             acc_h = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b_hi[s], acc_h, 0, 0, 0);
             acc_l = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b_lo[s], acc_l, 0, 0, 0);
+            if constexpr (Q32) {
+                const pd_v8h al = *reinterpret_cast<const pd_v8h *>(q_s[buf][1] + n * QROW + g * 16 + s * 32);
+                acc_l = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, b_hi[s], acc_l, 0, 0, 0);
+            }
         }
         // result register r of lane (n, g): query row 8*(r/4) + 4*g + r%4 of the tile, key column n
         const int t0 = tile * kPdTQ;
@@ -229,7 +284,9 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int row = 8 * (r / 4) + 4 * g + (r % 4);
-            const float sc = fmaf(acc_l[r], 1.f / kPdLoScale, acc_h[r]) * inv_scale;
+            float sc = fmaf(acc_l[r], 1.f / kPdLoScale, acc_h[r]) * inv_scale;
+            if constexpr (Q32)
+                sc *= qinv_s[buf][row];
             stage_s[buf][row * kPdStageStride + wave * 32 + n] = (key <= (int64_t)t0 + row + off) ? sc : -INFINITY;
         }
         LOOKAT_PD_PUT_Q(buf ^ 1)
@@ -264,19 +321,22 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
 }
 
 template <int DK, int M>
-static void launch_prefill_dense_case(const PrefillDenseArgs &a, hipStream_t st)
+static void launch_prefill_dense_case(const PrefillDenseArgs &a, bool q_fp32, hipStream_t st)
 {
     const int64_t wgs = (int64_t)((a.BH + 7) / 8 * 8) * a.panels;
-    hipLaunchKernelGGL((score_prefill_dense_kernel<DK, M>), dim3((unsigned)wgs), dim3(kPdThreads), 0, st, a);
+    if (q_fp32)
+        hipLaunchKernelGGL((score_prefill_dense_kernel<float, DK, M>), dim3((unsigned)wgs), dim3(kPdThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL((score_prefill_dense_kernel<__half, DK, M>), dim3((unsigned)wgs), dim3(kPdThreads), 0, st, a);
 }
 
-// fp16 queries, d_k in {64, 128}, m in {2, 4, 8, 16}: launches and returns true; otherwise returns false
-// and the caller takes the lookup-and-sum kernel.
-bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q, const float *codebooks,
+// d_k in {64, 128}, m in {2, 4, 8, 16}: launches and returns true; otherwise returns false and the caller
+// takes the lookup-and-sum kernel.
+bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q, bool q_fp32, const float *codebooks,
                           const uint8_t *codes, int64_t code_stride_bh, float *scores, hipStream_t st)
 {
     PrefillDenseArgs a;
-    a.q = static_cast<const __half *>(q);
+    a.q = q;
     a.codebooks = codebooks;
     a.codes = codes;
     a.scores = scores;
@@ -291,7 +351,7 @@ bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q
         return false;
 #define LOOKAT_PD_CASE(DK_, M_)                      \
     if (s->d_k == DK_ && s->m == M_) {               \
-        launch_prefill_dense_case<DK_, M_>(a, st);   \
+        launch_prefill_dense_case<DK_, M_>(a, q_fp32, st);   \
         return true;                                 \
     }
     LOOKAT_PD_CASE(64, 2)

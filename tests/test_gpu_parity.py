@@ -432,8 +432,8 @@ def _prefill_bars(got, ref, q, cb, codes, lut_ref, label):
 
 _PREFILL_NARROW = {}   # label -> entries checked / entries outside the table-entry bar
 
-# lookat_score_prefill has two kernels: blocks of 32 or more fp16 queries are scored as a dense product
-# against the keys' centroids on the matrix cores, everything else by lookup-and-sum in LDS.  "library"
+# lookat_score_prefill has two kernels: blocks of 32 or more queries are scored as a dense product against
+# the keys' centroids on the matrix cores, shorter blocks by lookup-and-sum in LDS.  "library"
 # takes the library's choice, "lookup" forces the lookup-and-sum kernel through its measurement-aid entry
 # point, so that it stays covered on the shapes the library no longer routes to it.
 _PREFILL_ENTRIES = {"library": ("lookat_score_prefill", "score_prefill"),
@@ -451,7 +451,8 @@ def _prefill_check(lk, case, cb, codes, path="library"):
 
 
 @pytest.mark.parametrize("d_k,m", [(128, 16), (128, 8), (64, 4), (64, 2), (64, 16)])
-@pytest.mark.parametrize("q_dtype,path", [("float16", "library"), ("float16", "lookup"), ("float32", "library")])
+@pytest.mark.parametrize("q_dtype,path", [("float16", "library"), ("float16", "lookup"), ("float32", "library"),
+                                          ("float32", "lookup")])
 @pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135), (64, 0), (40, 24), (300, 1300),
                                      (40, 2101), (100, 4200), (32, 0), (31, 97), (129, 3), (96, 160)])
 def test_score_prefill_parity(lk, d_k, m, q_dtype, path, T, extra):
@@ -459,7 +460,7 @@ def test_score_prefill_parity(lk, d_k, m, q_dtype, path, T, extra):
     are the tail of a longer cache (extra > 0), a single query, contexts beyond the 2048 keys whose codes
     the lookup kernel's scoring threads keep in registers (one and two further rounds of keys), L odd (scalar
     stores), key panels that end inside a 128-key panel or exactly on one, T on either side of the 32 queries
-    from which fp16 blocks go to the matrix cores."""
+    from which blocks go to the matrix cores."""
     L = T + extra
     cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)
     case = li.make_case(cfg, seed=5000 + d_k + m + T)

@@ -304,12 +304,12 @@ int lookat_attend_decode_launch_shape(const lookat_shape *shape, int64_t L, int3
  *     scores[b,h,t,l] = sum_i ( sum_j q[b,h,t, i*d_sub + j] * codebooks[h,i, codes[b,h,l,i], j] )
  * for visible l, and -inf elsewhere.  Nothing but `scores` is written: no table and no decoded key
  * leaves the chip.  Two kernels compute it, chosen by shape:
- *   - T >= 32: the double sum is taken as one dense product of the queries with the keys' centroids
+ *   - T >= 24: the double sum is taken as one dense product of the queries with the keys' centroids
  *     (fetched from the codebook by code) on the matrix cores; centroids, and fp32 queries, are scaled
  *     by a power of two and split into two fp16 terms (products exact; the product of two small terms,
  *     2^-22 of a product, is dropped), accumulation in fp32 over all d_k coordinates in the matrix
  *     unit's order;
- *   - T < 32: per-query tables built in LDS and summed by look-up (table entries accumulated in
+ *   - T < 24: per-query tables built in LDS and summed by look-up (table entries accumulated in
  *     fp32, the coordinates j in ascending groups of four whose inner order depends on the
  *     centroid; entries then summed in ascending i).
  * Either way |error| stays within 1e-4 of sum_i sum_j |q_j| |c_j|.

@@ -86,7 +86,7 @@ int lookat_probe_attend_decode_ticket(const lookat_shape *shape, int64_t L,
 
 /*
  * lookat_score_prefill forced onto its lookup-and-sum kernel (per-query tables built and gathered in LDS,
- * paper Sec. 3.5 as written), whatever the shape: lookat_score_prefill itself scores blocks of 32 or more
+ * paper Sec. 3.5 as written), whatever the shape: lookat_score_prefill itself scores blocks of 24 or more
  * queries as a dense product against the keys' centroids on the matrix cores.  Same arguments, results
  * and error behaviour as lookat_score_prefill; exists so that both kernels can be timed and checked against
  * the oracle on the same inputs.

@@ -475,10 +475,11 @@ static int dispatch_prefill(const lookat_shape *s, const PrefillArgs &a, hipStre
 bool launch_prefill_dense(const lookat_shape *s, int T, int64_t L, const void *q, bool q_fp32, const float *codebooks,
                           const uint8_t *codes, int64_t code_stride_bh, float *scores, hipStream_t st);
 
-// From this many queries per (b,h) on, blocks of queries are scored on the matrix cores: a 32-query
-// operand tile is then full, and the kernel is bound by the scores it writes; below it the
-// lookup-and-sum kernel, whose tiles hold four queries, wastes less.
-constexpr int kPfDenseMinT = 32;
+// From this many queries per (b,h) on, blocks of queries are scored on the matrix cores.  Its workgroups
+// spend their first microseconds fetching centroids, which a short block does not repay: measured at 4 x 32
+// heads, 4096 keys, d_k 128, m 16 (us per call, matrix cores / lookup-and-sum): T = 8: 40 / 22, 16: 40 / 34,
+// 24: 40 / 46, 32: 41 / 57, 64: 52 / 67, 256: 135 / 236.
+constexpr int kPfDenseMinT = 24;
 
 static int score_prefill_impl(const lookat_shape *shape, int32_t T, int64_t L, const void *q, lookat_dtype q_dtype,
                               const float *codebooks, const uint8_t *codes, int64_t code_stride_bh,

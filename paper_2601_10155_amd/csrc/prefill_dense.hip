@@ -36,7 +36,7 @@
 // same sum that the lookup-and-sum kernel is held to.
 // fp32 queries are split like the centroids (per query row, on their way into LDS); the products of the two
 // small terms (2^-22 of a product) are dropped.
-// Used for T >= 32, d_k in {64, 128}, d_sub a multiple of 4; everything else takes the lookup-and-sum kernel.
+// Used for T >= 24, d_k in {64, 128}, d_sub a multiple of 4; everything else takes the lookup-and-sum kernel.
 #include <type_traits>
 
 #include "common.h"

@@ -246,7 +246,7 @@ def test_config_c4_full_size_prefill(lk):
     case = li.torch_case(cfg, "cuda", layer=0)
     cb = lk.lookat_kmeans(case["calib"], case["cb_init"], 1)
     codes = lk.lookat_encode_keys(case["keys"], cb)
-    # both scoring kernels at the full size: the library's choice for this shape (fp16 queries, T >= 32: the
+    # both scoring kernels at the full size: the library's choice for this shape (T >= 24: the
     # dense product against the keys' centroids on the matrix cores) and the lookup-and-sum kernel, forced
     scores = lk.lookat_score_prefill(case["q"], cb, codes)
     scores_lookup = lk.lookat_probe_score_prefill_lookup(case["q"], cb, codes)

@@ -432,7 +432,7 @@ def _prefill_bars(got, ref, q, cb, codes, lut_ref, label):
 
 _PREFILL_NARROW = {}   # label -> entries checked / entries outside the table-entry bar
 
-# lookat_score_prefill has two kernels: blocks of 32 or more queries are scored as a dense product against
+# lookat_score_prefill has two kernels: blocks of 24 or more queries are scored as a dense product against
 # the keys' centroids on the matrix cores, shorter blocks by lookup-and-sum in LDS.  "library"
 # takes the library's choice, "lookup" forces the lookup-and-sum kernel through its measurement-aid entry
 # point, so that it stays covered on the shapes the library no longer routes to it.
@@ -454,12 +454,12 @@ def _prefill_check(lk, case, cb, codes, path="library"):
 @pytest.mark.parametrize("q_dtype,path", [("float16", "library"), ("float16", "lookup"), ("float32", "library"),
                                           ("float32", "lookup")])
 @pytest.mark.parametrize("T,extra", [(70, 0), (333, 0), (45, 50), (1, 0), (530, 135), (64, 0), (40, 24), (300, 1300),
-                                     (40, 2101), (100, 4200), (32, 0), (31, 97), (129, 3), (96, 160)])
+                                     (40, 2101), (100, 4200), (32, 0), (31, 97), (129, 3), (96, 160), (23, 41), (24, 0)])
 def test_score_prefill_parity(lk, d_k, m, q_dtype, path, T, extra):
     """Ragged query tiles (T not a multiple of 4 or of 32), one workgroup per (b,h) and several, queries that
     are the tail of a longer cache (extra > 0), a single query, contexts beyond the 2048 keys whose codes
     the lookup kernel's scoring threads keep in registers (one and two further rounds of keys), L odd (scalar
-    stores), key panels that end inside a 128-key panel or exactly on one, T on either side of the 32 queries
+    stores), key panels that end inside a 128-key panel or exactly on one, T on either side of the 24 queries
     from which blocks go to the matrix cores."""
     L = T + extra
     cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=d_k, m=m, n_calib=400, q_dtype=q_dtype)

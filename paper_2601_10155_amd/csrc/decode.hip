@@ -249,7 +249,7 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G
         st.m_run[g] = m_new;
     }
     if constexpr (MM) {
-        static_assert(DK == 128 && CH == 8 && G >= 4 && G <= 8, "matrix-core value sum: d_k = 128, 4 or 8 query heads");
+        static_assert(DK == 128 && CH % 4 == 0 && G >= 4 && G <= 8, "matrix-core value sum: d_k = 128, 4 or 8 query heads");
         if (__builtin_amdgcn_readfirstlane((int)moved)) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -273,7 +273,7 @@ __device__ __forceinline__ void consume_tile(const DecodeArgs &a, SoftmaxState<G
 #pragma unroll
         for (int c0 = 0; c0 < NLD; c0 += CH) {
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
+            for (int tt = 0; tt < CH / 4; ++tt) {
                 const uint32_t r_r = (uint32_t)(c0 / 4 + tt) * 4u + kg_;
                 const v4h bw = *reinterpret_cast<const __attribute__((address_space(3))) v4h *>(
                     pstage + r_r * 128u + ((n_ * 8u) ^ ((r_r >> 1) * 8u)));
@@ -432,9 +432,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     constexpr int LPR = DK / 8;            // lanes per value row (16 bytes per lane)
     constexpr int RPL = kWave / LPR;       // value rows covered by one wave-wide load
     constexpr int NLD = kTile / RPL;       // wave-wide loads per tile (= LPR)
-    constexpr int CH = NLD < 8 ? NLD : 8;  // loads kept in flight together
-    constexpr int NT = WAVES * kWave;
     constexpr bool MM = (G >= 4 && DK == 128 && M != 0);   // weighted value sum on the matrix cores
+    // loads kept in flight together: 8 KB of a tile; the whole 16 KB tile where the matrix cores take the value sum
+    // (its accumulators are half the size, and a second request round in the middle of a tile is a second
+    // exposed round trip at two wavefronts per SIMD)
+    constexpr int CH = MM ? NLD : (NLD < 8 ? NLD : 8);
+    constexpr int NT = WAVES * kWave;
 
     extern __shared__ __align__(16) float smem[];
     float *lut_s = smem;                                   // [G][m][256]
@@ -884,7 +887,7 @@ static int launch_gqa(const DecodeArgs &a, dim3 grid, hipStream_t st)
     const size_t lds = gqa_lds_bytes(G, a.m, DK, GW);
 #define LOOKAT_GQA_CASE(M_)                                                                                    \
     case M_: {                                                                                                 \
-        auto kern = decode_split_kernel<DK, M_, GW, (G <= 4 ? 4 : (GW == kDecWaves ? 3 : 2)), void, G>;        \
+        auto kern = decode_split_kernel<DK, M_, GW, ((DK == 128 && G >= 4) ? 2 : (G <= 4 ? 4 : (GW == kDecWaves ? 3 : 2))), void, G>; \
         if (lds > 64 * 1024) {                                                                                 \
             /* allow more than 64 KB of dynamic LDS: idempotent, so every call makes it (no shared flag) */   \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                          \

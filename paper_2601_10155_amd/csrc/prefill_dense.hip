@@ -213,10 +213,32 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
                 const int i = dim0 / DSUB;
                 const uint32_t code = (cw[i / 4] >> (8 * (i % 4))) & 0xffu;
                 raw[s][u] = *reinterpret_cast<const pd_v4f *>(cb_h + ((int64_t)i * kCentroids + code) * DSUB + dim0 % DSUB);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    cmax = fmaxf(cmax, fabsf(raw[s][u][e]));
             }
+        // ---- rows that cannot see any key of the panel: -inf.  Here, behind the centroid requests and ahead of
+        // their use: the stores keep the memory system busy while the centroids arrive, and the wait for
+        // the centroids (older in the in-order counter) does not wait for the stores ----
+        {
+            const int rows_masked = tile_first * kPdTQ;     // rows before the first tile that sees the panel (< T)
+            const pd_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (a.vec4) {
+                // kPdPanel / 4 threads cover the panel's columns of one row; the workgroup covers 8 rows per pass
+                const int c4 = tid % (kPdPanel / 4);
+                if (l0 + 4 * c4 < a.L)
+                    for (int r = tid / (kPdPanel / 4); r < rows_masked; r += kPdThreads / (kPdPanel / 4))
+                        __builtin_nontemporal_store(ninf, reinterpret_cast<pd_v4f *>(scores_bh + (int64_t)r * a.L + l0 + 4 * c4));
+            } else {
+                const int c = tid & (kPdPanel - 1);
+                if (l0 + c < a.L)
+                    for (int r = tid / kPdPanel; r < rows_masked; r += kPdThreads / kPdPanel)
+                        scores_bh[(int64_t)r * a.L + l0 + c] = -INFINITY;
+            }
+        }
+
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                cmax = fmaxf(cmax, fabsf(raw[s][e / 4][e % 4]));
         cmax = wave_max(cmax);
         int ex = (int)((__float_as_uint(cmax) >> 23) & 0xffu) - 127;   // floor(log2(cmax)) for normal numbers
         if (cmax == 0.f)
@@ -234,24 +256,6 @@ __global__ __launch_bounds__(kPdThreads, 2) void score_prefill_dense_kernel(cons
                 b_hi[s][e] = wh;
                 b_lo[s][e] = (_Float16)((w - (float)wh) * kPdLoScale);   // exact difference and scaling, one rounding
             }
-    }
-
-    // ---- rows that cannot see any key of the panel: -inf ----
-    {
-        const int rows_masked = tile_first * kPdTQ;     // rows before the first tile that sees the panel (< T)
-        const pd_v4f ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (a.vec4) {
-            // kPdPanel / 4 threads cover the panel's columns of one row; the workgroup covers 8 rows per pass
-            const int c4 = tid % (kPdPanel / 4);
-            if (l0 + 4 * c4 < a.L)
-                for (int r = tid / (kPdPanel / 4); r < rows_masked; r += kPdThreads / (kPdPanel / 4))
-                    __builtin_nontemporal_store(ninf, reinterpret_cast<pd_v4f *>(scores_bh + (int64_t)r * a.L + l0 + 4 * c4));
-        } else {
-            const int c = tid & (kPdPanel - 1);
-            if (l0 + c < a.L)
-                for (int r = tid / kPdPanel; r < rows_masked; r += kPdThreads / kPdPanel)
-                    scores_bh[(int64_t)r * a.L + l0 + c] = -INFINITY;
-        }
     }
 
     LOOKAT_PD_PUT_Q(0)

@@ -49,7 +49,7 @@ COUNTED_TRAFFIC = {
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0, "fused"),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0, (2, 16)),
     ("C4", "score_prefill"): (37033.6, 1.0, 2.0, 2.10989e6, None),   # lookup-and-sum kernel; FETCH_SIZE at 2 KiB per count (calibration of the 2 GiB read)
-    ("C4", "score_prefill_dense"): (41312.7, 1.0, 2.0, 2.09812e6, None),   # matrix-core kernel
+    ("C4", "score_prefill_dense"): (41175.7, 1.0, 2.0, 2.09782e6, None),   # matrix-core kernel
 }
 
 

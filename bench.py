@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM traffic per launch of the dominant kernel, from hardware counters (they cannot be read
 # inside this process: two separate `rocprofv3 --pmc` runs of this script, FETCH_SIZE then
-# WRITE_SIZE, recorded under profiles/*_hbm_counters.md).  Entry: (FETCH_SIZE per dispatch,
+# WRITE_SIZE, recorded in the counter summaries under profiles/).  Entry: (FETCH_SIZE per dispatch,
 # FETCH_SIZE of lookat::stream_read_kernel in the same run, KiB that kernel reads, WRITE_SIZE
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {

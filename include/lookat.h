@@ -178,6 +178,10 @@ int lookat_attend_decode_noalloc(const lookat_shape *shape, int64_t L,
  *     s[b,hq,l]   = sum_i lut[b,hq,i, codes[b, hq/group, l, i]]
  *     out[b,hq,:] = sum_l softmax_l(scale * s[b,hq,:]) * values[b, hq/group, l, :]
  * but the codes and values of a key/value head are streamed once for its `group` query heads.
+ * With d_k = 128 and group 4 or 8 the weighted value sum runs on the matrix cores: each softmax
+ * weight enters as two fp16 terms (22 bits), the fp16 values exactly, accumulation in fp32; the
+ * sum of weights stays an fp32 sum of the unsplit weights.  Other shapes accumulate with fp32
+ * multiply-adds as lookat_attend_decode does.
  *
  *   shape           B, H = number of KEY/VALUE heads, d_k, m, K; query heads = H * group
  *   group           1, 2, 4 or 8 (1 forwards to lookat_attend_decode)

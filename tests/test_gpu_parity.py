@@ -794,6 +794,89 @@ def test_ticket_merge_probe_matches_oracle(lk, d_k, m, B, H, L, splits):
         assert int(tickets.abs().max()) == 0, "ticket counters not back at zero"
 
 
+# ---------------------------------------------------------------- HIP graphs ----------
+
+
+def _capture(fn):
+    """fn recorded into a graph on torch's capture stream, after one warm-up call on a side stream."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    torch.cuda.synchronize()
+    return graph
+
+
+@pytest.mark.parametrize("g,d_k,m,L,splits", [(4, 128, 8, 3000, 3), (1, 64, 4, 1024, 0), (2, 64, 16, 1537, 2)])
+def test_decode_step_graph_replays_equal_eager(lk, g, d_k, m, L, splits):
+    """The fused step (ranges plus merge kernel where it splits) recorded into a graph: every one of three
+    replays, with eager launches of the same entry point on another context length and synchronisations in
+    between, leaves the code cache and the outputs bit-identical to the eager call, which meets the oracle."""
+    B, H, Lmax = 2, 2, L + 29
+    c = _step_case("C3", B, H, Lmax, L, d_k, m, "float16", 9100 + d_k + m + g + L, "recipe", g=g)
+    q, k_new, cb, values = dev(c["q"]), dev(c["k_new"]), dev(c["cb"]), dev(c["values"])
+    cache = torch.full((B, H, Lmax, m), 0x5A, dtype=torch.uint8, device="cuda")
+    cache[:, :, :L - 1] = dev(c["codes"][:, :, :L - 1])
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    out = torch.zeros((B, H * g, d_k), dtype=torch.float32, device="cuda")
+    other = torch.zeros_like(out)
+
+    def step():
+        lk.lookat_decode_step_gqa(q, k_new, cb, cache[:, :, :L], values[:, :, :L], c["scale"], num_splits=splits,
+                                  workspace=ws, out=out)
+
+    step()
+    torch.cuda.synchronize()
+    eager_out, eager_cache = out.clone(), cache.clone()
+    assert np.array_equal(eager_cache.cpu().numpy()[:, :, :L], c["codes"])
+    assert_out_close(eager_out.cpu().numpy(), c["out"], "decode_step_gqa before capture", c["scores"], c["scale"])
+    graph = _capture(step)
+    for replay in range(3):
+        cache[:, :, L - 1] = 0x5A
+        out.fill_(float("nan"))
+        ws.fill_(0xFF)
+        # eager work of the program's own between the replays: the same entry point on a shorter context
+        lk.lookat_decode_step_gqa(q, k_new, cb, cache[:, :, :L - 7], values[:, :, :L - 7], c["scale"],
+                                  num_splits=splits, out=other)
+        torch.cuda.synchronize()
+        cache[:, :, L - 8] = eager_cache[:, :, L - 8]
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cache, eager_cache), f"code cache after replay {replay}"
+        assert torch.equal(out, eager_out), f"outputs after replay {replay}"
+
+
+@pytest.mark.parametrize("q_dtype,T,L", [("float16", 96, 256), ("float32", 130, 333), ("float16", 8, 200)])
+def test_score_prefill_graph_replays_equal_eager(lk, q_dtype, T, L):
+    """Block scoring recorded into a graph (the matrix-core kernel for T >= 24, fp16 and split-fp32 queries;
+    the lookup kernel below): three replays into a poisoned output, eager calls on another block in between."""
+    cfg = li.shrink(li.CONFIGS["C4"], B=2, H=3, L=L, T=T, d_k=128, m=16, n_calib=400, q_dtype=q_dtype)
+    case = li.make_case(cfg, seed=9200 + T)
+    cb = case["cb_init"]
+    codes = dev(oracle.encode_keys(case["keys"], cb))
+    q, cbd = dev(case["q"]), dev(cb)
+    scores = torch.zeros((2, 3, T, L), dtype=torch.float32, device="cuda")
+    lk.lookat_score_prefill(q, cbd, codes, scores_out=scores)
+    torch.cuda.synchronize()
+    eager = scores.clone()
+    lut_ref = oracle.build_lut(case["q"], cb)
+    _prefill_bars(eager.cpu().numpy(), oracle.score_prefill(lut_ref, codes.cpu().numpy()), case["q"], cb,
+                  codes.cpu().numpy(), lut_ref, "score_prefill, before capture")
+    graph = _capture(lambda: lk.lookat_score_prefill(q, cbd, codes, scores_out=scores))
+    for replay in range(3):
+        scores.fill_(float("nan"))
+        lk.lookat_score_prefill(q[:, :, :T - 3].contiguous(), cbd, codes[:, :, :L - 5])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(scores, eager), f"scores after replay {replay}"
+
+
 def test_probe_stream_read_shapes_run(lk):
     """Every launch shape of the read probe streams the buffer without writing anything."""
     buf = torch.arange(1 << 18, dtype=torch.int32, device="cuda")

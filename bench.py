@@ -40,7 +40,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # per dispatch in KiB).  bytes = (fetch * known_KiB / stream_fetch + write) * 1024.
 COUNTED_TRAFFIC = {
     # key: (workload, fused step?) -> (FETCH_SIZE, stream FETCH_SIZE, stream KiB, WRITE_SIZE KiB, launch shape counted)
-    # launch shape: "fused" = the 512-thread fused-step instance, one range per (b,h); else (ranges, wavefronts) of
+    # launch shape: "fused" = the 512-thread fused-step instance, one range per (b,h); "fused, paired" = its 1024-thread
+    # form that serves two batch entries of a head per workgroup; else (ranges, wavefronts) of
     # lookat_attend_decode as lookat_attend_decode_launch_shape reports them.
     ("C1", True): (1249.5, 776.004, 1536.0, 3.375, "fused"),
     ("C1", False): (826.5, 776.004, 1536.0, 3.0, (1, 4)),
@@ -290,7 +291,8 @@ def main():
     achieved = bytes_per_launch / us_per_launch / 1e3   # GB/s
     stats = per_launch_stats(torch, fused_only if fused else decode_only, layers, n_launch)
     stats_alone = per_launch_stats(torch, decode_only, layers, n_launch) if fused else stats
-    launch_shape = "fused" if (fused and not fused_split) else \
+    paired = fused and not fused_split and lk.decode_step_entries_per_workgroup(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L) == 2
+    launch_shape = ("fused, paired" if paired else "fused") if (fused and not fused_split) else \
         (None if fused else lk.attend_decode_launch_shape(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, splits))
 
     # plain read stream over the same value caches: what the HBM read path delivers here
@@ -335,7 +337,8 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "lookat::decode_split_kernel" + (" (fused step instance)" if fused else ""),
+            "kernel": "lookat::decode_split_kernel" + ((" (fused step instance, two batch entries of a head per workgroup)"
+                                                         if paired else " (fused step instance)") if fused else ""),
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
@@ -411,6 +414,21 @@ def run_probes(torch, lk, cfg, layers, scale, sink, time_launches, n_launch):
     }
     if cfg.B * cfg.H >= 256:   # the same kernel with one whole (b,h) per workgroup: nothing to merge
         out["ticket_merge"]["us_per_launch_one_range"] = time_launches(lambda ly: ticket(ly, 1))
+    # the fused step with one and with two batch entries of a head per workgroup (two: the codebook is fetched
+    # once per pair); lookat_decode_step takes `library_choice` of them
+    if cfg.B % 2 == 0 and cfg.d_k == 64 and cfg.m in (2, 4, 8, 16) and hasattr(layers[0], "q_step"):
+        ly0 = layers[0]
+        one = lk.lookat_probe_decode_step_entries(1, ly0.q_step, ly0.k_step, ly0.cb, ly0.codes, ly0.values, scale).clone()
+        two = lk.lookat_probe_decode_step_entries(2, ly0.q_step, ly0.k_step, ly0.cb, ly0.codes, ly0.values, scale)
+        torch.cuda.synchronize()
+        out["decode_step_entries_per_workgroup"] = {
+            "library_choice": lk.decode_step_entries_per_workgroup(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L),
+            "us_per_launch_one": time_launches(lambda ly: lk.lookat_probe_decode_step_entries(
+                1, ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)),
+            "us_per_launch_two": time_launches(lambda ly: lk.lookat_probe_decode_step_entries(
+                2, ly.q_step, ly.k_step, ly.cb, ly.codes, ly.values, scale, out=ly.out)),
+            "max_abs_diff_two_vs_one": float((two - one).abs().max()),
+        }
     return out
 
 

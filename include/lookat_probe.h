@@ -98,6 +98,24 @@ int lookat_probe_score_prefill_lookup(const lookat_shape *shape, int32_t T, int6
                                       float *scores,
                                       void *stream);
 
+/*
+ * lookat_decode_step with the number of batch entries a workgroup serves chosen by the caller instead of
+ * by the library (see lookat_decode_step_entries_per_workgroup): 1 = one (b,h) per 512-thread workgroup;
+ * 2 = one 1024-thread workgroup serves (b, h) and (b + 1, h), fetches the head's codebook rows (paper
+ * Sec. 3.4 for the new key's codes, Sec. 3.5 for the tables) once and computes both entries' tables and
+ * distances from them.  Same arguments, results (bit for bit) and error behaviour as lookat_decode_step;
+ * 2 needs an even B and d_k = 64 (LOOKAT_ERR_UNSUPPORTED otherwise); any other count: LOOKAT_ERR_SHAPE.
+ * Exists so that both instances can be timed and checked on any shape.
+ */
+int lookat_probe_decode_step_entries(const lookat_shape *shape, int32_t entries_per_workgroup, int64_t L,
+                                     const void *q, const void *k_new, lookat_dtype qk_dtype,
+                                     const float *codebooks,
+                                     uint8_t *codes, int64_t code_stride_bh,
+                                     const void *values, int64_t value_stride_bh,
+                                     float scale,
+                                     float *out,
+                                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,10 @@ def load_library():
         lib.lookat_attend_decode_gqa.restype = ctypes.c_int
         lib.lookat_decode_step.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, vp, vp]
         lib.lookat_decode_step.restype = ctypes.c_int
+        lib.lookat_decode_step_entries_per_workgroup.argtypes = [sp, i64]
+        lib.lookat_decode_step_entries_per_workgroup.restype = i32
+        lib.lookat_probe_decode_step_entries.argtypes = [sp, i32, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, vp, vp]
+        lib.lookat_probe_decode_step_entries.restype = ctypes.c_int
         lib.lookat_decode_step_split_workspace_bytes.argtypes = [sp, i64, i32]
         lib.lookat_decode_step_split_workspace_bytes.restype = sz
         lib.lookat_decode_step_split.argtypes = [sp, i64, vp, vp, ctypes.c_int, vp, vp, i64, vp, i64, f32, i32, vp, sz, vp, vp]
@@ -326,6 +330,21 @@ def lookat_decode_step(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Te
     return _decode_step(q, k_new, codebooks, codes, values, scale, out, None, None)
 
 
+def decode_step_entries_per_workgroup(B: int, H: int, d_k: int, m: int, L: int) -> int:
+    """Batch entries one workgroup of lookat_decode_step serves for this problem (1 or 2; 0: no kernel)."""
+    shape = _Shape(B, H, d_k, m, 256)
+    return int(load_library().lookat_decode_step_entries_per_workgroup(ctypes.byref(shape), L))
+
+
+def lookat_probe_decode_step_entries(entries_per_workgroup: int, q: torch.Tensor, k_new: torch.Tensor,
+                                     codebooks: torch.Tensor, codes: torch.Tensor, values: torch.Tensor, scale: float,
+                                     out: torch.Tensor | None = None) -> torch.Tensor:
+    """lookat_decode_step on the kernel instance that serves `entries_per_workgroup` (1 or 2) batch entries of
+    a head per workgroup (2: even B, d_k = 64; measurement aid)."""
+    return _decode_step(q, k_new, codebooks, codes, values, scale, out, None, None,
+                        _entries=int(entries_per_workgroup))
+
+
 def lookat_decode_step_split(q: torch.Tensor, k_new: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor,
                              values: torch.Tensor, scale: float, num_splits: int = 0,
                              workspace: torch.Tensor | None = None, out: torch.Tensor | None = None) -> torch.Tensor:
@@ -378,7 +397,7 @@ def decode_step_split_workspace_bytes(B: int, H: int, d_k: int, m: int, L: int, 
     return int(load_library().lookat_decode_step_split_workspace_bytes(ctypes.byref(shape), L, num_splits))
 
 
-def _decode_step(q, k_new, codebooks, codes, values, scale, out, num_splits, workspace):
+def _decode_step(q, k_new, codebooks, codes, values, scale, out, num_splits, workspace, _entries=None):
     lib = load_library()
     q = _dev(q, "q").contiguous()
     k_new = _dev(k_new, "k_new").contiguous()
@@ -400,6 +419,12 @@ def _decode_step(q, k_new, codebooks, codes, values, scale, out, num_splits, wor
         raise ValueError("out must be contiguous fp32 [B,H,d_k]")
     shape = _Shape(B, H, d_k, m, 256)
     if num_splits is None:
+        if _entries is not None:
+            _check(lib.lookat_probe_decode_step_entries(ctypes.byref(shape), _entries, L, q.data_ptr(), k_new.data_ptr(),
+                                                        _dtype_tag(q), cb.data_ptr(), codes.data_ptr(), cs,
+                                                        values.data_ptr(), vs, float(scale), out.data_ptr(),
+                                                        _stream(values)))
+            return out
         _check(lib.lookat_decode_step(ctypes.byref(shape), L, q.data_ptr(), k_new.data_ptr(), _dtype_tag(q),
                                       cb.data_ptr(), codes.data_ptr(), cs, values.data_ptr(), vs, float(scale),
                                       out.data_ptr(), _stream(values)))

@@ -16,6 +16,7 @@
 #include <type_traits>
 
 #include "decode_common.h"
+#include "lookat_probe.h"
 
 namespace lookat {
 
@@ -99,14 +100,25 @@ __device__ __forceinline__ DecodeArgs rebuild_args(LOOKAT_DECODE_HEAD_PARAMS, co
 // Workgroup id -> (bh, split).  Consecutive workgroup ids land on different dies, each
 // with its own L2; this mapping keeps all splits of one (b,h) on one die so that its
 // table is fetched into a single L2.
-__device__ __forceinline__ bool map_block(const DecodeArgs &a, int &bh, int &split)
+__device__ __forceinline__ bool map_block_n(const DecodeArgs &a, int count, int &unit, int &split)
 {
     const int bid = blockIdx.x;
     const int xcd = bid % kXcds;
     const int slot = bid / kXcds;
-    bh = (slot / a.splits) * kXcds + xcd;
+    unit = (slot / a.splits) * kXcds + xcd;
     split = slot % a.splits;
-    return bh < a.BH;
+    return unit < count;
+}
+__device__ __forceinline__ bool map_block(const DecodeArgs &a, int &bh, int &split)
+{
+    return map_block_n(a, a.BH, bh, split);
+}
+
+// LDS of one batch entry of the fused step (table, per-wavefront partial results, the encoder's per-wavefront
+// minima and indices), rounded to 16 bytes: the distance between the two entries' blocks of a paired workgroup.
+__host__ __device__ constexpr size_t step_pair_lds_bytes(int m, int d_k)
+{
+    return ((((size_t)m * 256 + (size_t)8 * (d_k + 2)) * sizeof(float) + (size_t)m * 4 * (sizeof(double) + sizeof(int))) + 15) / 16 * 16;
 }
 
 // ---- pieces of the fused decode step ---------------------------------------------------
@@ -342,16 +354,32 @@ __device__ __forceinline__ void load_centroid_rows(float (&row)[GS][DSUB], const
 // scores the new key and appends its codes; the others build the table alone).
 // G > 1 (grouped queries): bh is the key/value head; the G query heads bh*G .. bh*G+G-1 each get their
 // table (lut_s[g][i][c]) from the one pass over the key/value head's codebook rows.
-template <typename FT, int DK, int M, int G = 1>
-__device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int tid, int lane, int wave, float *lut_s,
-                                              double *enc_d, int *enc_c, bool encode)
+template <typename FT, int DK, int M, int G = 1, int NB = 1>
+__device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int part, int tid, int lane, int wave,
+                                              float *lut_s, double *enc_d, int *enc_c, int lds_stride, bool encode)
 {
+    // NB = 2 (two batch entries of one head per workgroup, each with its own 256 table builders): the builders
+    // of entry `part` fetch the codebook rows of subspaces part*M/2 .. part*M/2 + M/2 - 1 only and from each row
+    // compute the table entries and distances of BOTH entries (bh and bh + H; their LDS blocks lie lds_stride
+    // bytes apart), so that the pair reads the head's codebook once instead of twice.
+    static_assert(NB == 1 || (NB == 2 && G == 1 && M % 2 == 0), "paired batch entries: ungrouped, even m");
     constexpr int DSUB = DK / M;
-    constexpr int GS = (64 / DSUB) < 1 ? 1 : ((64 / DSUB) > M ? M : (64 / DSUB));
+    constexpr int MS = M / NB;            // subspaces this builder group covers
+    // rows held at once: 64 registers; paired entries keep two entries' distances alive, so short rows
+    // (d_sub < 16) are taken 16 registers at a time there
+    constexpr int kRowRegs = (NB == 2 && DSUB < 16) ? 16 : 64;
+    constexpr int GS0 = (kRowRegs / DSUB) < 1 ? 1 : ((kRowRegs / DSUB) > MS ? MS : (kRowRegs / DSUB));
+    constexpr int GS = (MS % GS0 == 0) ? GS0 : 1;
     float frow[GS][DSUB];
+    const int ibase = part * MS;
     const float *__restrict__ cbh = a.codebooks + (int64_t)(bh % a.H) * M * kCentroids * DSUB + (int64_t)tid * DSUB;
-    const UniformWords qg = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + (uintptr_t)bh * G * DK * sizeof(FT));
-    const UniformWords kg = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + (uintptr_t)bh * DK * sizeof(FT));
+    UniformWords qg[NB], kg[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const uintptr_t row = (uintptr_t)(bh + nb * a.H);
+        qg[nb] = (UniformWords)(reinterpret_cast<uintptr_t>(a.q) + row * G * DK * sizeof(FT));
+        kg[nb] = (UniformWords)(reinterpret_cast<uintptr_t>(a.k_new) + row * DK * sizeof(FT));
+    }
     // The scalar loads of q and k_new are issued a subspace at a time, each shortly before its use, and
     // the rows are cold (written by the previous layer's kernels): every 128-byte line would cost a
     // memory round trip in the middle of the table arithmetic.  One word of every line is requested
@@ -360,46 +388,55 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
     uint32_t touched = 0;
     if constexpr (G == 1) {
 #pragma unroll
-        for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
-            touched |= qg[o / 4];
+        for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-        for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
-            touched |= kg[o / 4];
-    }
-    load_centroid_rows<DSUB, GS>(frow, cbh, 0);
+            for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
+                touched |= qg[nb][o / 4];
 #pragma unroll
-    for (int i0 = 0; i0 < M; i0 += GS) {
-        if (i0 > 0)
-            load_centroid_rows<DSUB, GS>(frow, cbh, i0);
-        double dv[GS], dm[GS];
-#pragma unroll
-        for (int g = 0; g < GS; ++g) {
-            const int i = i0 + g;
-#pragma unroll
-            for (int hq = 0; hq < G; ++hq) {
-                float e = 0.f;
-#pragma unroll
-                for (int j = 0; j < DSUB; ++j)
-                    e = fmaf(uniform_elem<FT>(qg, hq * DK + i * DSUB + j), frow[g][j], e);
-                lut_s[(hq * M + i) * kCentroids + tid] = e;
-            }
-            if (G == 1 || encode) {
-                dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg, i * DSUB, frow[g]), tid);
-                dm[g] = dv[g];
-            }
+            for (int o = 0; o < (int)(DK * sizeof(FT)); o += 128)
+                touched |= kg[nb][o / 4];
         }
-        // Ungrouped, the distances are evaluated in every range and published only where the new key is
-        // scored: the branch would cost more than the arithmetic.  With grouped queries the ranges that
-        // do not hold the new key skip them (eight heads' tables already keep those wavefronts busy).
-        if (G == 1 || encode) {
-            dmin_wave<GS>(dm);
+    }
+    load_centroid_rows<DSUB, GS>(frow, cbh, ibase);
+#pragma unroll
+    for (int i0 = 0; i0 < MS; i0 += GS) {
+        if (i0 > 0)
+            load_centroid_rows<DSUB, GS>(frow, cbh, ibase + i0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            float *lut_nb = reinterpret_cast<float *>(reinterpret_cast<char *>(lut_s) + nb * lds_stride);
+            double *encd_nb = reinterpret_cast<double *>(reinterpret_cast<char *>(enc_d) + nb * lds_stride);
+            int *encc_nb = reinterpret_cast<int *>(reinterpret_cast<char *>(enc_c) + nb * lds_stride);
+            double dv[GS], dm[GS];
 #pragma unroll
             for (int g = 0; g < GS; ++g) {
-                // lowest lane that holds the wave minimum = lowest centroid index of this wave
-                const uint64_t holders = __ballot(dv[g] == dm[g]);
-                if (lane == 0 && encode) {
-                    enc_d[(i0 + g) * kDecWaves + wave] = dm[g];
-                    enc_c[(i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+                const int i = ibase + i0 + g;
+#pragma unroll
+                for (int hq = 0; hq < G; ++hq) {
+                    float e = 0.f;
+#pragma unroll
+                    for (int j = 0; j < DSUB; ++j)
+                        e = fmaf(uniform_elem<FT>(qg[nb], hq * DK + i * DSUB + j), frow[g][j], e);
+                    lut_nb[(hq * M + i) * kCentroids + tid] = e;
+                }
+                if (G == 1 || encode) {
+                    dv[g] = argmin_value(step_sq_dist<FT, DSUB>(kg[nb], i * DSUB, frow[g]), tid);
+                    dm[g] = dv[g];
+                }
+            }
+            // Ungrouped, the distances are evaluated in every range and published only where the new key is
+            // scored: the branch would cost more than the arithmetic.  With grouped queries the ranges that
+            // do not hold the new key skip them (eight heads' tables already keep those wavefronts busy).
+            if (G == 1 || encode) {
+                dmin_wave<GS>(dm);
+#pragma unroll
+                for (int g = 0; g < GS; ++g) {
+                    // lowest lane that holds the wave minimum = lowest centroid index of this wave
+                    const uint64_t holders = __ballot(dv[g] == dm[g]);
+                    if (lane == 0 && encode) {
+                        encd_nb[(ibase + i0 + g) * kDecWaves + wave] = dm[g];
+                        encc_nb[(ibase + i0 + g) * kDecWaves + wave] = wave * kWave + (int)__builtin_ctzll(holders);
+                    }
                 }
             }
         }
@@ -414,14 +451,20 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int t
 // whose tables (contiguous in memory) are all staged in LDS; codes and values are streamed once.
 // PF: tiles of a wavefront requested before anything else is done (1, or more for the fused step,
 // whose table build and key encoding would otherwise leave the memory pipe idle for microseconds).
-template <int DK, int M, int WAVES, int OCC, typename FT = void, int G = 1, int PF = 1>
-__global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_DECODE_HEAD_PARAMS,
-                                                                         const DecodeLate late)
+// NB = 2 (fused step only): the workgroup has 2 x WAVES wavefronts and serves TWO batch entries of one head,
+// (b, h) and (b + 1, h).  Each half is a complete copy of the roles above with its own LDS block; the only
+// thing shared is the codebook, of which each half's table builders fetch half the subspaces and compute
+// both entries' table rows and distances.  The head's codebook then crosses from L2 to the compute units
+// once per pair instead of once per (b,h).  Both halves execute the same barriers (same L, same ranges).
+template <int DK, int M, int WAVES, int OCC, typename FT = void, int G = 1, int PF = 1, int NB = 1>
+__global__ __launch_bounds__(WAVES *NB *kWave, OCC) void decode_split_kernel(LOOKAT_DECODE_HEAD_PARAMS,
+                                                                             const DecodeLate late)
 {
     const DecodeArgs a = rebuild_args(p_BH, p_splits, p_H, p_table, p_codes, p_values, p_code_stride, p_value_stride,
                                       p_L, p_kps, p_scale_log2e, late, !std::is_void<FT>::value);
     constexpr bool FUSED = !std::is_void<FT>::value;
     static_assert(!FUSED || (WAVES == 2 * kDecWaves && M != 0), "fused step: 512 threads, compile-time m");
+    static_assert(NB == 1 || (NB == 2 && FUSED && G == 1), "paired batch entries: ungrouped fused step only");
     // Fused step: the eight wavefronts take two roles until the table exists.  The first four
     // (256 threads, thread c = centroid c) fetch the codebook rows, build the table and encode the
     // new key (step_prologue) and request no tile before that is done; the other four request
@@ -439,17 +482,30 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
     constexpr int CH = MM ? NLD : (NLD < 8 ? NLD : 8);
     constexpr int NT = WAVES * kWave;
 
-    extern __shared__ __align__(16) float smem[];
+    extern __shared__ __align__(16) float smem_all[];
+    // which of the workgroup's NB batch entries this wavefront belongs to (scalar), and its LDS block
+    const int hf = (NB == 1) ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / (WAVES * kWave));
+    constexpr int kHalfBytes = (NB == 1) ? 0 : (int)step_pair_lds_bytes(M, DK);
+    float *smem = reinterpret_cast<float *>(reinterpret_cast<char *>(smem_all) + hf * kHalfBytes);
     float *lut_s = smem;                                   // [G][m][256]
     float *red_s = smem + G * (M ? M : a.m) * kCentroids;  // [WAVES][G][DK + 2]
     double *enc_d = reinterpret_cast<double *>(red_s + WAVES * G * (DK + 2));   // fused step: [M][WAVES] minima,
     int *enc_c = reinterpret_cast<int *>(enc_d + (M ? M : 1) * kDecWaves);     //             then [M][WAVES] indices
 
     int bh, split;
-    if (!map_block(a, bh, split))
-        return;
+    if constexpr (NB == 1) {
+        if (!map_block(a, bh, split))
+            return;
+    } else {
+        // a.BH / 2 pairs are dealt to the workgroups as (b,h) pairs are otherwise: pair p = head p % H of the
+        // batch entries 2*(p / H) and 2*(p / H) + 1
+        int pair;
+        if (!map_block_n(a, a.BH / 2, pair, split))
+            return;
+        bh = 2 * (pair / a.H) * a.H + pair % a.H + hf * a.H;
+    }
     const int m = M ? M : a.m;
-    const int tid = threadIdx.x;
+    const int tid = (NB == 1) ? (int)threadIdx.x : (int)threadIdx.x - hf * (WAVES * kWave);   // within the half
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // in a scalar register: role branches are scalar branches
     const bool builds_table = FUSED && wave < kDecWaves;
@@ -512,7 +568,12 @@ __global__ __launch_bounds__(WAVES *kWave, OCC) void decode_split_kernel(LOOKAT_
             // issue ahead of the streamers that share the SIMD: the codebook requests must enter the
             // compute unit's memory queue before the tile requests fill it
             __builtin_amdgcn_s_setprio(3);
-            step_prologue<FT, DK, M, G>(a, bh, tid, lane, wave, lut_s, enc_d, enc_c, k1 == (uint32_t)a.L);
+            // (paired entries: the LDS blocks and the (b,h) index are handed over as entry 0's)
+            step_prologue<FT, DK, M, G, NB>(a, bh - hf * a.H, hf, tid, lane, wave,
+                                            reinterpret_cast<float *>(reinterpret_cast<char *>(lut_s) - hf * kHalfBytes),
+                                            reinterpret_cast<double *>(reinterpret_cast<char *>(enc_d) - hf * kHalfBytes),
+                                            reinterpret_cast<int *>(reinterpret_cast<char *>(enc_c) - hf * kHalfBytes),
+                                            kHalfBytes, k1 == (uint32_t)a.L);
             __builtin_amdgcn_s_setprio(0);
         } else {
             LOOKAT_REQUEST_FIRST_TILES()
@@ -887,6 +948,49 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
     }
 }
 
+// Two batch entries of one head per workgroup (1024 threads): see decode_split_kernel, NB = 2.
+// When the library takes it.  A compute unit holds two 512-thread workgroups of the fused step or one paired
+// one, and a launch is as slow as its most loaded compute unit.  Up to 256 (b,h) every workgroup has a
+// compute unit to itself and pairing only halves the parallelism (192 (b,h) x 1024 keys, d_k = 64, m = 4,
+// graph replays: 7.2 us single, 9.5 us paired); from 257 to 512 (b,h) some compute units carry two (b,h)
+// either way and the pairs halve the codebook traffic (264: 11.0 -> 9.8 us; 384: 11.8 -> 11.0; 504:
+// 14.4 -> 13.0); beyond 512 the pairs need a second round of workgroups where single entries still
+// fit two to a compute unit (528: 17.7 single, 20.3 paired).  Short contexts (512 keys: 8.8 / 8.9 us) and m >= 8
+// (m = 8: 11.4 / 11.8 us; m = 16: 14.4 / 15.1) measured no gain.
+static bool step_pairs_entries(const lookat_shape *s, int group, int64_t L, int S)
+{
+    const int64_t BH = (int64_t)s->B * s->H;
+    return group == 1 && S == 1 && !(s->B & 1) && s->d_k == 64 && (s->m == 2 || s->m == 4) && BH > 256 && BH <= 512 &&
+           L >= 768;
+}
+
+template <int DK, typename FT>
+static bool launch_step_pair(const DecodeArgs &a, dim3 grid, hipStream_t st)
+{
+    dim3 block(2 * kStepWaves * kWave);
+    const size_t lds = 2 * step_pair_lds_bytes(a.m, DK);
+    switch (a.m) {
+    case 2:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
+                           LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
+        return true;
+    case 4:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 4, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
+                           LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
+        return true;
+    case 8:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 8, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
+                           LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
+        return true;
+    case 16:
+        hipLaunchKernelGGL((decode_split_kernel<DK, 16, kStepWaves, 4, FT, 1, 1, 2>), grid, block, lds, st,
+                           LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
+        return true;
+    default:
+        return false;
+    }
+}
+
 // Grouped queries: 256-thread workgroups; four wavefronts per SIMD up to G = 4 (G accumulator sets
 // per lane fit 128 registers), two for G = 8.
 // LDS of a grouped-query workgroup: the group's tables and the per-wavefront partial results.
@@ -1010,8 +1114,14 @@ namespace lookat {
 static int decode_step_impl(const char *who, const lookat_shape *shape, int group, int64_t L, const void *q,
                             const void *k_new, int qk_dtype, const float *codebooks, uint8_t *codes,
                             int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale, int S,
-                            void *workspace, size_t workspace_bytes, float *out, void *stream)
+                            void *workspace, size_t workspace_bytes, float *out, void *stream, int force_entries = 0)
 {
+    // (at d_k = 128 two entries' tile registers and distances do not fit the 128 registers of a 1024-thread workgroup)
+    // force_entries: 0 = the library's choice of batch entries per workgroup, 1 or 2 = that many (measurement aid)
+    if (force_entries == 2 && (group != 1 || (shape->B & 1) || shape->d_k != 64))
+        return fail(LOOKAT_ERR_UNSUPPORTED, "paired batch entries need an even batch, ungrouped queries and d_k = 64; got B=%d group=%d d_k=%d",
+                    shape->B, group, shape->d_k);
+    const bool paired = force_entries == 2 || (force_entries == 0 && step_pairs_entries(shape, group, L, S));
     if (L <= 0)
         return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
     if (qk_dtype != LOOKAT_F16 && qk_dtype != LOOKAT_F32)
@@ -1047,7 +1157,8 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
         if (!aligned16(workspace))
             return fail(LOOKAT_ERR_ALIGN, "workspace must be 16-byte aligned");
     }
-    const int64_t nblocks = (BH + kXcds - 1) / kXcds * kXcds * S;
+    const int64_t units = paired ? BH / 2 : BH;   // workgroups per range
+    const int64_t nblocks = (units + kXcds - 1) / kXcds * kXcds * S;
     if (nblocks > 0x7fffffffLL)
         return fail(LOOKAT_ERR_UNSUPPORTED, "B*H*num_splits=%lld workgroups exceed one launch", (long long)nblocks);
 
@@ -1076,7 +1187,10 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
     dim3 grid((unsigned)nblocks);
     if (group == 1) {
         bool ok;
-        if (shape->d_k == 64)
+        if (paired) {
+            ok = (qk_dtype == LOOKAT_F16) ? launch_step_pair<64, __half>(a, grid, st)
+                                          : launch_step_pair<64, float>(a, grid, st);
+        } else if (shape->d_k == 64)
             ok = (qk_dtype == LOOKAT_F16) ? launch_step<64, __half>(a, grid, st) : launch_step<64, float>(a, grid, st);
         else
             ok = (qk_dtype == LOOKAT_F16) ? launch_step<128, __half>(a, grid, st) : launch_step<128, float>(a, grid, st);
@@ -1110,6 +1224,35 @@ extern "C" int lookat_decode_step(const lookat_shape *shape, int64_t L, const vo
         return rc;
     return decode_step_impl("lookat_decode_step", shape, 1, L, q, k_new, qk_dtype, codebooks, codes, code_stride_bh, values,
                             value_stride_bh, scale, 1, nullptr, 0, out, stream);
+}
+
+extern "C" int32_t lookat_decode_step_entries_per_workgroup(const lookat_shape *shape, int64_t L)
+{
+    using namespace lookat;
+    clear_error();
+    if (check_shape(shape) != LOOKAT_OK || L <= 0)
+        return 0;
+    const bool m_ok = shape->m == 2 || shape->m == 4 || shape->m == 8 || shape->m == 16;
+    if (!m_ok || (shape->d_k != 64 && shape->d_k != 128))
+        return 0;
+    return step_pairs_entries(shape, 1, L, 1) ? 2 : 1;
+}
+
+extern "C" int lookat_probe_decode_step_entries(const lookat_shape *shape, int32_t entries_per_workgroup, int64_t L,
+                                                const void *q, const void *k_new, lookat_dtype qk_dtype,
+                                                const float *codebooks, uint8_t *codes, int64_t code_stride_bh,
+                                                const void *values, int64_t value_stride_bh, float scale, float *out,
+                                                void *stream)
+{
+    using namespace lookat;
+    clear_error();
+    if (int rc = check_shape(shape))
+        return rc;
+    if (entries_per_workgroup != 1 && entries_per_workgroup != 2)
+        return fail(LOOKAT_ERR_SHAPE, "entries_per_workgroup=%d must be 1 or 2", entries_per_workgroup);
+    return decode_step_impl("lookat_probe_decode_step_entries", shape, 1, L, q, k_new, qk_dtype, codebooks, codes,
+                            code_stride_bh, values, value_stride_bh, scale, 1, nullptr, 0, out, stream,
+                            entries_per_workgroup);
 }
 
 extern "C" size_t lookat_decode_step_split_workspace_bytes(const lookat_shape *shape, int64_t L, int32_t num_splits)

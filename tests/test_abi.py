@@ -172,6 +172,22 @@ def test_decode_step_argument_errors(lib):
     assert f(*a) == E_UNSUP
 
 
+def test_decode_step_entries_per_workgroup(lib):
+    """Which fused-step instance a shape resolves to (host only): pairs of batch entries only for even B,
+    d_k = 64, m in {2, 4}, 257..512 (b,h) pairs and contexts of 768 keys or more."""
+    f = lib.lookat_decode_step_entries_per_workgroup
+    def n(B, H, d_k, m, L):
+        s = Shape(B, H, d_k, m, 256)
+        return f(ctypes.byref(s), L)
+    assert n(32, 12, 64, 4, 1024) == 2 and n(32, 12, 64, 2, 1024) == 2 and n(22, 12, 64, 4, 768) == 2
+    assert n(42, 12, 64, 4, 4096) == 2 and n(16, 32, 64, 4, 1024) == 2
+    assert n(20, 12, 64, 4, 1024) == 1      # 240 (b,h): every workgroup has a compute unit to itself
+    assert n(44, 12, 64, 4, 1024) == 1      # 528 (b,h): the pairs would need a second round
+    assert n(31, 12, 64, 4, 1024) == 1      # odd batch
+    assert n(32, 12, 64, 8, 1024) == 1 and n(32, 12, 128, 4, 1024) == 1 and n(32, 12, 64, 4, 767) == 1
+    assert n(32, 12, 32, 4, 1024) == 0 and n(32, 12, 64, 4, 0) == 0 and f(None, 5) == 0
+
+
 def test_decode_step_split_argument_errors(lib):
     """No call here reaches a launch: every argument list fails a host-side check."""
     s = Shape(1, 4, 128, 8, 256)

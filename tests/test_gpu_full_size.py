@@ -112,10 +112,18 @@ def test_config_c2_full_size_fused_step_and_three_calls(lk):
     cache = codes.clone()
     cache[:, :, -1] = 0xEE
     q1, k1 = case["q"][:, :, 0].float(), case["keys"][:, :, -1].contiguous()
+    # at this size the library serves two batch entries of a head per workgroup ...
+    assert lk.decode_step_entries_per_workgroup(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L) == 2
     out1 = lk.lookat_decode_step(q1, k1, cb, cache, case["values"], scale)
     assert torch.equal(cache, codes)
     assert float((out1 - out).abs().max()) <= 1e-5
     _check_step_slabs(cfg, case, cb, cache, q1, k1, out1, scale, picks, "C2 full size, fused step, recipe queries")
+    # ... and on the first 20 batch entries (240 (b,h)) one: the same arithmetic per (b,h), so the same bits
+    assert lk.decode_step_entries_per_workgroup(20, cfg.H, cfg.d_k, cfg.m, cfg.L) == 1
+    cache[:20, :, -1] = 0xEE
+    out20 = lk.lookat_decode_step(q1[:20].contiguous(), k1[:20].contiguous(), cb, cache[:20], case["values"][:20], scale)
+    assert torch.equal(cache, codes)
+    assert torch.equal(out20, out1[:20])
     # a peaked softmax (queries times 8), then the appended key carrying most of the weight
     cache[:, :, -1] = 0xEE
     out8 = lk.lookat_decode_step(q1 * 8, k1, cb, cache, case["values"], scale)

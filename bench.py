@@ -45,7 +45,7 @@ COUNTED_TRAFFIC = {
     # lookat_attend_decode as lookat_attend_decode_launch_shape reports them.
     ("C1", True): (1249.5, 776.004, 1536.0, 3.375, "fused"),
     ("C1", False): (826.5, 776.004, 1536.0, 3.0, (1, 4)),
-    ("C2", True): (26393.0, 24584.0, 49152.0, 108.0, "fused"),
+    ("C2", True): (26394.5, 24586.0, 49152.0, 108.0, "fused, paired"),
     ("C2", False): (26144.5, 24584.0, 49152.0, 96.0, (1, 4)),
     ("C3", True): (1.0838e6, 1.04858e6, 2097152.0, 136.0, "fused"),
     ("C3", False): (1.08264e6, 1.04858e6, 2097152.0, 268.0, (2, 16)),

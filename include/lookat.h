@@ -212,8 +212,9 @@ int lookat_attend_decode_gqa(const lookat_shape *shape, int32_t group, int64_t L
  *   2. the query's lookup tables are built as in lookat_build_lut (Sec. 3.5), kept on chip;
  *   3. the query attends over the L cached keys as in lookat_attend_decode (Algorithm 1).
  * Results equal those of the three separate calls (codes bit for bit; out within fp32
- * rounding).  Each workgroup re-reads its head's codebook from L2; with few (b,h) pairs and a
- * long context the three separate calls (which can cut the sequence into ranges) are faster.
+ * rounding).  Each workgroup re-reads its head's codebook from L2 (where the library pairs two batch
+ * entries of a head in one workgroup, see lookat_decode_step_entries_per_workgroup, once for both); with
+ * few (b,h) pairs and a long context lookat_decode_step_split, which cuts the sequence into ranges, is faster.
  *
  *   L          cached keys per (b,h) INCLUDING the new one, >= 1
  *   q, k_new   [B,H,d_k], both of type qk_dtype (fp16 or fp32), 16-byte aligned, dense

@@ -827,6 +827,67 @@ def test_ticket_merge_probe_matches_oracle(lk, d_k, m, B, H, L, splits):
         assert int(tickets.abs().max()) == 0, "ticket counters not back at zero"
 
 
+# ---------------------------------------------------------------- seeded random shapes ----------
+
+def _random_shape_cases(n, seed):
+    """n seeded draws of (B, H, L, cache padding, (d_k, m), query heads per key/value head, ranges, dtype):
+    combinations the hand-picked grids above do not enumerate (odd batch and head counts against every
+    kernel instance, short and ragged contexts in padded caches, every group size with every split count)."""
+    rng = np.random.default_rng(seed)
+    shapes = [(64, 4), (64, 2), (64, 8), (64, 16), (128, 8), (128, 16), (128, 2), (128, 4)]
+    cases = []
+    for _ in range(n):
+        d_k, m = shapes[int(rng.integers(len(shapes)))]
+        B, H = int(rng.integers(1, 7)), int(rng.integers(1, 6))
+        L = int([rng.integers(1, 130), rng.integers(130, 1200), rng.integers(1200, 4200)][int(rng.integers(3))])
+        pad = int(rng.integers(0, 3)) * int(rng.integers(1, 90))
+        g = int(rng.choice([1, 1, 2, 4, 8]))
+        if g == 8 and m == 16:      # eight 16 KB tables and the reduction buffer exceed the 160 KB of LDS
+            g = 4
+        splits = int(rng.choice([0, 0, 1, 2, 3, 5]))
+        dtype = ["float16", "float32"][int(rng.integers(2))]
+        cases.append((B, H, L, pad, d_k, m, g, splits, dtype))
+    return cases
+
+
+@pytest.mark.parametrize("B,H,L,pad,d_k,m,g,splits,qk_dtype", _random_shape_cases(48, 20260110))
+def test_random_shapes_three_calls_and_fused_step(lk, B, H, L, pad, d_k, m, g, splits, qk_dtype):
+    """On each drawn shape: the three library calls (encode into a padded cache, tables, attention with
+    scores, grouped or not, on views of the padded caches) and the fused step on a cache whose last row is
+    stale, all against the oracle's three steps."""
+    Lmax = L + pad
+    c = _step_case("C3" if d_k == 128 else "C2", B, H, Lmax, L, d_k, m, qk_dtype, 9500 + B * 7 + H * 5 + L + m + g, "recipe", g=g)
+    scale = c["scale"]
+    # three calls, on views of caches with Lmax rows per (b,h)
+    cache = torch.full((B, H, Lmax, m), 0x3C, dtype=torch.uint8, device="cuda")
+    lk.lookat_encode_keys(dev(c["keys"]), dev(c["cb"]), cache=cache, position=0)
+    got = cache.cpu().numpy()
+    assert np.array_equal(got[:, :, :L], c["codes"]) and (got[:, :, L:] == 0x3C).all()
+    values = dev(c["values"])                                   # [B,H,Lmax,d_k]
+    cb_q = np.repeat(c["cb"], g, axis=0)
+    lut_ref = oracle.build_lut(c["q"][:, :, None], cb_q)[:, :, 0]
+    lut = lk.lookat_build_lut(dev(c["q"][:, :, None]), dev(cb_q)).view(B, H * g, m, 256)
+    assert_lut_close(lut.cpu().numpy()[:, :, None], c["q"][:, :, None], cb_q, lut_ref[:, :, None])
+    scores = torch.empty((B, H * g, L), dtype=torch.float32, device="cuda")
+    lut_d = dev(lut_ref)                                        # attention from the oracle's table: one table, two readers
+    if g == 1:
+        out = lk.lookat_attend_decode(lut_d, cache[:, :, :L], values[:, :, :L], scale, num_splits=splits, scores_out=scores)
+    else:
+        out = lk.lookat_attend_decode_gqa(lut_d, cache[:, :, :L], values[:, :, :L], scale, num_splits=splits,
+                                          scores_out=scores)
+    assert_scores_close(scores.cpu().numpy(), lut_ref, np.repeat(c["codes"], g, axis=1), c["scores"])
+    assert_out_close(out.cpu().numpy(), c["out"], "random shapes, attention", c["scores"], scale)
+    # fused step
+    if g == 1 and splits == 0:
+        call = lk.lookat_decode_step
+    elif g == 1:
+        call = lambda q, k, cb, codes, vals, sc: lk.lookat_decode_step_split(q, k, cb, codes, vals, sc, num_splits=splits)
+    else:
+        call = lambda q, k, cb, codes, vals, sc: lk.lookat_decode_step_gqa(q, k, cb, codes, vals, sc, num_splits=splits)
+    out2, _ = _run_step(lk, c, L, Lmax, 0x77, call)
+    assert_out_close(out2.cpu().numpy(), c["out"], "random shapes, fused step", c["scores"], scale)
+
+
 # ---------------------------------------------------------------- HIP graphs ----------
 
 

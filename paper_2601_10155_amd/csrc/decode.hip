@@ -118,7 +118,8 @@ __device__ __forceinline__ bool map_block(const DecodeArgs &a, int &bh, int &spl
 // minima and indices), rounded to 16 bytes: the distance between the two entries' blocks of a paired workgroup.
 __host__ __device__ constexpr size_t step_pair_lds_bytes(int m, int d_k)
 {
-    return ((((size_t)m * 256 + (size_t)8 * (d_k + 2)) * sizeof(float) + (size_t)m * 4 * (sizeof(double) + sizeof(int))) + 15) / 16 * 16;
+    return ((((size_t)m * kCentroids + (size_t)(2 * kDecWaves) * (d_k + 2)) * sizeof(float) +
+             (size_t)m * kDecWaves * (sizeof(double) + sizeof(int))) + 15) / 16 * 16;
 }
 
 // ---- pieces of the fused decode step ---------------------------------------------------
@@ -1116,8 +1117,9 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
                             int64_t code_stride_bh, const void *values, int64_t value_stride_bh, float scale, int S,
                             void *workspace, size_t workspace_bytes, float *out, void *stream, int force_entries = 0)
 {
-    // (at d_k = 128 two entries' tile registers and distances do not fit the 128 registers of a 1024-thread workgroup)
-    // force_entries: 0 = the library's choice of batch entries per workgroup, 1 or 2 = that many (measurement aid)
+    // force_entries: 0 = the library's choice of batch entries per workgroup, 1 or 2 = that many (measurement aid).
+    // (At d_k = 128 two entries' tile registers and distances do not fit the 128 registers of a 1024-thread
+    // workgroup: no paired instance.)
     if (force_entries == 2 && (group != 1 || (shape->B & 1) || shape->d_k != 64))
         return fail(LOOKAT_ERR_UNSUPPORTED, "paired batch entries need an even batch, ungrouped queries and d_k = 64; got B=%d group=%d d_k=%d",
                     shape->B, group, shape->d_k);

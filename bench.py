@@ -416,7 +416,8 @@ def run_probes(torch, lk, cfg, layers, scale, sink, time_launches, n_launch):
         out["ticket_merge"]["us_per_launch_one_range"] = time_launches(lambda ly: ticket(ly, 1))
     # the fused step with one and with two batch entries of a head per workgroup (two: the codebook is fetched
     # once per pair); lookat_decode_step takes `library_choice` of them
-    if cfg.B % 2 == 0 and cfg.d_k == 64 and cfg.m in (2, 4, 8, 16) and hasattr(layers[0], "q_step"):
+    if cfg.B % 2 == 0 and ((cfg.d_k == 64 and cfg.m in (2, 4, 8, 16)) or (cfg.d_k == 128 and cfg.m in (4, 8, 16))) \
+            and hasattr(layers[0], "q_step"):
         ly0 = layers[0]
         one = lk.lookat_probe_decode_step_entries(1, ly0.q_step, ly0.k_step, ly0.cb, ly0.codes, ly0.values, scale).clone()
         two = lk.lookat_probe_decode_step_entries(2, ly0.q_step, ly0.k_step, ly0.cb, ly0.codes, ly0.values, scale)

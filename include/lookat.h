@@ -236,8 +236,8 @@ int lookat_decode_step(const lookat_shape *shape, int64_t L,
 
 /* Batch entries one workgroup of lookat_decode_step serves for this problem (host only, no HIP call):
  * 1, or 2 where the library pairs the entries (b, h) and (b + 1, h) so that their head's codebook is
- * fetched once for both (even B, d_k = 64, m in {2, 4}, 257..512 (b,h) pairs, L >= 768; results do not
- * depend on it, bit for bit).  0 if the shape is invalid or the step has no kernel for it.  Exists so
+ * fetched once for both (even B, 257..512 (b,h) pairs, and d_k = 64 with m in {2, 4} and L >= 768, or
+ * d_k = 128 with m = 4 and L >= 512 or m = 8 and L >= 2048; results do not depend on it, bit for bit).  0 if the shape is invalid or the step has no kernel for it.  Exists so
  * that tests and measurements can state which kernel instance a shape exercises. */
 int32_t lookat_decode_step_entries_per_workgroup(const lookat_shape *shape, int64_t L);
 

@@ -104,7 +104,8 @@ int lookat_probe_score_prefill_lookup(const lookat_shape *shape, int32_t T, int6
  * 2 = one 1024-thread workgroup serves (b, h) and (b + 1, h), fetches the head's codebook rows (paper
  * Sec. 3.4 for the new key's codes, Sec. 3.5 for the tables) once and computes both entries' tables and
  * distances from them.  Same arguments, results (bit for bit) and error behaviour as lookat_decode_step;
- * 2 needs an even B and d_k = 64 (LOOKAT_ERR_UNSUPPORTED otherwise); any other count: LOOKAT_ERR_SHAPE.
+ * 2 needs an even B and d_k = 64, or d_k = 128 with m > 2 (LOOKAT_ERR_UNSUPPORTED otherwise); any other
+ * count: LOOKAT_ERR_SHAPE.
  * Exists so that both instances can be timed and checked on any shape.
  */
 int lookat_probe_decode_step_entries(const lookat_shape *shape, int32_t entries_per_workgroup, int64_t L,

@@ -366,9 +366,9 @@ __device__ __forceinline__ void step_prologue(const DecodeArgs &a, int bh, int p
     static_assert(NB == 1 || (NB == 2 && G == 1 && M % 2 == 0), "paired batch entries: ungrouped, even m");
     constexpr int DSUB = DK / M;
     constexpr int MS = M / NB;            // subspaces this builder group covers
-    // rows held at once: 64 registers; paired entries keep two entries' distances alive, so short rows
-    // (d_sub < 16) are taken 16 registers at a time there
-    constexpr int kRowRegs = (NB == 2 && DSUB < 16) ? 16 : 64;
+    // rows held at once: 64 registers; paired entries keep two entries' distances alive, so there short rows
+    // (d_sub < 16) are taken 16 registers at a time and, at d_k = 128 (twice the tile registers), longer ones 32
+    constexpr int kRowRegs = (NB == 2) ? ((DSUB < 16) ? 16 : (DK == 128 ? 32 : 64)) : 64;
     constexpr int GS0 = (kRowRegs / DSUB) < 1 ? 1 : ((kRowRegs / DSUB) > MS ? MS : (kRowRegs / DSUB));
     constexpr int GS = (MS % GS0 == 0) ? GS0 : 1;
     float frow[GS][DSUB];
@@ -957,12 +957,22 @@ static bool launch_step(const DecodeArgs &a, dim3 grid, hipStream_t st)
 // either way and the pairs halve the codebook traffic (264: 11.0 -> 9.8 us; 384: 11.8 -> 11.0; 504:
 // 14.4 -> 13.0); beyond 512 the pairs need a second round of workgroups where single entries still
 // fit two to a compute unit (528: 17.7 single, 20.3 paired).  Short contexts (512 keys: 8.8 / 8.9 us) and m >= 8
-// (m = 8: 11.4 / 11.8 us; m = 16: 14.4 / 15.1) measured no gain.
+// (m = 8: 11.4 / 11.8 us; m = 16: 14.4 / 15.1) measured no gain at d_k = 64.
+// d_k = 128 (fp16 queries, graph replays, single / paired us): m = 4: 384 (b,h) x 1024 keys 23.7 / 22.3, 512 x 1024
+// 30.8 / 27.1, 320 x 1024 23.3 / 20.4, 384 x 4096 72.6 / 66.7, 512 x 512 20.2 / 17.9; m = 8: 384 x 1024 21.6 / 22.3,
+// 512 x 1024 27.4 / 26.6, 512 x 512 17.3 / 17.5, 384 x 4096 71.9 / 69.5, 320 x 2048 38.3 / 33.4, 512 x 2048 (fp32)
+// 51.2 / 49.3: taken from 2048 keys on; m = 16: 384 x 1024 23.7 / 24.8, 512 x 1024 27.8 / 30.2: not taken;
+// m = 2 (one codebook row = 64 registers) has no paired instance at d_k = 128: it would spill.
 static bool step_pairs_entries(const lookat_shape *s, int group, int64_t L, int S)
 {
     const int64_t BH = (int64_t)s->B * s->H;
-    return group == 1 && S == 1 && !(s->B & 1) && s->d_k == 64 && (s->m == 2 || s->m == 4) && BH > 256 && BH <= 512 &&
-           L >= 768;
+    if (group != 1 || S != 1 || (s->B & 1) || BH <= 256 || BH > 512)
+        return false;
+    if (s->d_k == 64)
+        return (s->m == 2 || s->m == 4) && L >= 768;
+    if (s->d_k == 128)
+        return (s->m == 4 && L >= 512) || (s->m == 8 && L >= 2048);
+    return false;
 }
 
 template <int DK, typename FT>
@@ -972,9 +982,12 @@ static bool launch_step_pair(const DecodeArgs &a, dim3 grid, hipStream_t st)
     const size_t lds = 2 * step_pair_lds_bytes(a.m, DK);
     switch (a.m) {
     case 2:
-        hipLaunchKernelGGL((decode_split_kernel<DK, 2, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
-                           LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
-        return true;
+        if constexpr (DK == 64) {
+            hipLaunchKernelGGL((decode_split_kernel<DK, 2, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
+                               LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
+            return true;
+        }
+        return false;
     case 4:
         hipLaunchKernelGGL((decode_split_kernel<DK, 4, kStepWaves, 4, FT, 1, kStepPrefetch, 2>), grid, block, lds, st,
                            LOOKAT_DECODE_HEAD_ARGS(a, true), late_of(a));
@@ -1118,11 +1131,12 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
                             void *workspace, size_t workspace_bytes, float *out, void *stream, int force_entries = 0)
 {
     // force_entries: 0 = the library's choice of batch entries per workgroup, 1 or 2 = that many (measurement aid).
-    // (At d_k = 128 two entries' tile registers and distances do not fit the 128 registers of a 1024-thread
-    // workgroup: no paired instance.)
-    if (force_entries == 2 && (group != 1 || (shape->B & 1) || shape->d_k != 64))
-        return fail(LOOKAT_ERR_UNSUPPORTED, "paired batch entries need an even batch, ungrouped queries and d_k = 64; got B=%d group=%d d_k=%d",
-                    shape->B, group, shape->d_k);
+    // (At d_k = 128 with m = 2 a codebook row alone is 64 registers: two entries' state does not fit the 128
+    // registers of a 1024-thread workgroup, so there is no paired instance.)
+    if (force_entries == 2 && (group != 1 || (shape->B & 1) || (shape->d_k != 64 && (shape->d_k != 128 || shape->m == 2))))
+        return fail(LOOKAT_ERR_UNSUPPORTED,
+                    "paired batch entries need an even batch, ungrouped queries and d_k = 64 or d_k = 128 with m > 2; "
+                    "got B=%d group=%d d_k=%d m=%d", shape->B, group, shape->d_k, shape->m);
     const bool paired = force_entries == 2 || (force_entries == 0 && step_pairs_entries(shape, group, L, S));
     if (L <= 0)
         return fail(LOOKAT_ERR_SHAPE, "L=%lld must be positive", (long long)L);
@@ -1190,8 +1204,12 @@ static int decode_step_impl(const char *who, const lookat_shape *shape, int grou
     if (group == 1) {
         bool ok;
         if (paired) {
-            ok = (qk_dtype == LOOKAT_F16) ? launch_step_pair<64, __half>(a, grid, st)
-                                          : launch_step_pair<64, float>(a, grid, st);
+            if (shape->d_k == 64)
+                ok = (qk_dtype == LOOKAT_F16) ? launch_step_pair<64, __half>(a, grid, st)
+                                              : launch_step_pair<64, float>(a, grid, st);
+            else
+                ok = (qk_dtype == LOOKAT_F16) ? launch_step_pair<128, __half>(a, grid, st)
+                                              : launch_step_pair<128, float>(a, grid, st);
         } else if (shape->d_k == 64)
             ok = (qk_dtype == LOOKAT_F16) ? launch_step<64, __half>(a, grid, st) : launch_step<64, float>(a, grid, st);
         else

@@ -174,7 +174,8 @@ def test_decode_step_argument_errors(lib):
 
 def test_decode_step_entries_per_workgroup(lib):
     """Which fused-step instance a shape resolves to (host only): pairs of batch entries only for even B,
-    d_k = 64, m in {2, 4}, 257..512 (b,h) pairs and contexts of 768 keys or more."""
+    257..512 (b,h) pairs, and d_k = 64 with m in {2, 4} from 768 keys or d_k = 128 with m = 4 from 512 keys / m = 8
+    from 2048 keys."""
     f = lib.lookat_decode_step_entries_per_workgroup
     def n(B, H, d_k, m, L):
         s = Shape(B, H, d_k, m, 256)
@@ -184,7 +185,11 @@ def test_decode_step_entries_per_workgroup(lib):
     assert n(20, 12, 64, 4, 1024) == 1      # 240 (b,h): every workgroup has a compute unit to itself
     assert n(44, 12, 64, 4, 1024) == 1      # 528 (b,h): the pairs would need a second round
     assert n(31, 12, 64, 4, 1024) == 1      # odd batch
-    assert n(32, 12, 64, 8, 1024) == 1 and n(32, 12, 128, 4, 1024) == 1 and n(32, 12, 64, 4, 767) == 1
+    assert n(32, 12, 64, 8, 1024) == 1 and n(32, 12, 64, 4, 767) == 1
+    assert n(12, 32, 128, 4, 512) == 2 and n(12, 32, 128, 4, 511) == 1          # d_k = 128: m = 4 from 512 keys,
+    assert n(12, 32, 128, 8, 2048) == 2 and n(12, 32, 128, 8, 2047) == 1        # m = 8 from 2048,
+    assert n(12, 32, 128, 16, 4096) == 1 and n(12, 32, 128, 2, 4096) == 1       # m = 16 and m = 2 never
+    assert n(8, 32, 128, 8, 32768) == 1                                         # 256 (b,h): one each
     assert n(32, 12, 32, 4, 1024) == 0 and n(32, 12, 64, 4, 0) == 0 and f(None, 5) == 0
 
 

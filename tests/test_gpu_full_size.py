@@ -280,3 +280,35 @@ def test_config_c4_full_size_prefill(lk):
         # the materialised tables of the same queries (matrix-core path) agree with the oracle's
         lut_gpu = lk.lookat_build_lut(case["q"][b:b + 1, h:h + 1].contiguous(), cb[h:h + 1].contiguous())
         _lut_close(lut_gpu.cpu().numpy(), _slab(case["q"], b, h), cbn[h:h + 1], lut_ref)
+
+
+@pytest.mark.parametrize("B,H,L,d_k,m,qk", [(12, 32, 1024, 128, 4, torch.float16), (10, 32, 2048, 128, 8, torch.float32),
+                                            (22, 12, 768, 64, 2, torch.float16), (42, 12, 1024, 64, 4, torch.float32)])
+def test_decode_step_where_the_library_pairs_batch_entries(lk, B, H, L, d_k, m, qk):
+    """Shapes at which lookat_decode_step itself serves two batch entries of a head per workgroup (257..512
+    (b,h)), other than C2: the whole launch bit-identical to the one-entry instance, sampled (b,h) against
+    the oracle's three steps (queries scaled so that the softmax is peaked: a wrong code row would show)."""
+    assert lk.decode_step_entries_per_workgroup(B, H, d_k, m, L) == 2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4100 + B + L + m)
+    cb = torch.randn((H, m, 256, d_k // m), generator=gen, device="cuda") * 0.5
+    cache = torch.randint(0, 256, (B, H, L, m), generator=gen, device="cuda", dtype=torch.uint8)
+    values = torch.randn((B, H, L, d_k), generator=gen, device="cuda").half()
+    q = (torch.randn((B, H, d_k), generator=gen, device="cuda") * 1.5).to(qk)
+    k_new = (torch.randn((B, H, d_k), generator=gen, device="cuda") * 0.5).to(qk)
+    scale = 1.0 / math.sqrt(d_k)
+    cache[:, :, -1] = 0xEE
+    c2 = cache.clone()
+    out = lk.lookat_decode_step(q, k_new, cb, cache, values, scale)
+    out1 = lk.lookat_probe_decode_step_entries(1, q, k_new, cb, c2, values, scale)
+    assert torch.equal(cache, c2) and torch.equal(out, out1)
+    cbn = cb.cpu().numpy()
+    rng = np.random.default_rng(B * 100 + H)
+    picks = {(0, 0), (1, 0), (B - 1, H - 1), (B - 2, H - 1)} | {(int(rng.integers(B)), int(rng.integers(H))) for _ in range(4)}
+    for b, h in sorted(picks):
+        codes_slab = _slab(cache, b, h)
+        new_ref = oracle.encode_keys(_slab(k_new[:, :, None], b, h), cbn[h:h + 1])
+        assert np.array_equal(codes_slab[:, :, -1:], new_ref), f"appended code row of slab {(b, h)}"
+        lut_ref = oracle.build_lut(_slab(q[:, :, None], b, h), cbn[h:h + 1])[:, :, 0]
+        out_ref, s_ref = oracle.attend_decode(lut_ref, codes_slab, _slab(values, b, h), scale, want_scores=True)
+        assert_out_close(_slab(out, b, h), out_ref, "fused step where the library pairs batch entries", s_ref, scale)

@@ -639,11 +639,11 @@ def test_decode_step_peaked_and_aligned(lk, d_k, m, qk_dtype, kind, L):
     assert_out_close(out.cpu().numpy(), c["out"], f"decode_step, {kind} queries", c["scores"], c["scale"])
 
 
-@pytest.mark.parametrize("m", [2, 4, 8, 16])
+@pytest.mark.parametrize("d_k,m", [(64, 2), (64, 4), (64, 8), (64, 16), (128, 4), (128, 8), (128, 16)])
 @pytest.mark.parametrize("qk_dtype", ["float16", "float32"])
 @pytest.mark.parametrize("kind", ["recipe", "peaked", "aligned"])
 @pytest.mark.parametrize("B,L", [(2, 1), (2, 65), (4, 512), (6, 1024), (4, 1537), (2, 4133)])
-def test_decode_step_paired_entries_match_oracle_and_fused_step(lk, m, qk_dtype, kind, B, L):
+def test_decode_step_paired_entries_match_oracle_and_fused_step(lk, d_k, m, qk_dtype, kind, B, L):
     """The instance that serves two batch entries of a head per workgroup (each half's table builders fetch
     half the subspaces' codebook rows and compute both entries' tables and distances): codes and outputs
     against the oracle on the three kinds of input, and bit-identical to lookat_decode_step.  H = 3 and
@@ -651,10 +651,10 @@ def test_decode_step_paired_entries_match_oracle_and_fused_step(lk, m, qk_dtype,
     if kind != "recipe" and qk_dtype == "float32":
         pytest.skip("peaked and aligned inputs run in fp16 (the dtype only changes how q and k_new are read)")
     H, Lmax = 3, L + 67
-    c = _step_case("C2", B, H, Lmax, L, 64, m, qk_dtype, 6900 + m + B, kind)
+    c = _step_case("C2" if d_k == 64 else "C3", B, H, Lmax, L, d_k, m, qk_dtype, 6900 + d_k + m + B, kind)
     out, cache = _run_step(lk, c, L, Lmax, 0xAB, functools.partial(lk.lookat_probe_decode_step_entries, 2))
     assert_out_close(out.cpu().numpy(), c["out"], f"decode_step, paired entries, {kind} queries", c["scores"], c["scale"])
-    assert lk.decode_step_entries_per_workgroup(B, H, 64, m, L) == 1
+    assert lk.decode_step_entries_per_workgroup(B, H, d_k, m, L) == 1
     for single in (lk.lookat_decode_step, functools.partial(lk.lookat_probe_decode_step_entries, 1)):
         out1, cache1 = _run_step(lk, c, L, Lmax, 0xAB, single)
         assert torch.equal(cache, cache1)
@@ -667,7 +667,7 @@ def test_decode_step_paired_entries_rejects_odd_batch_and_wide_heads(lk):
         _run_step(lk, c, 70, 100, 0xAB, functools.partial(lk.lookat_probe_decode_step_entries, 2))
     with pytest.raises(lk.LookatError):
         _run_step(lk, c, 70, 100, 0xAB, functools.partial(lk.lookat_probe_decode_step_entries, 3))
-    c = _step_case("C3", 2, 2, 100, 70, 128, 8, "float16", 6991, "recipe")
+    c = _step_case("C3", 2, 2, 100, 70, 128, 2, "float16", 6991, "recipe")   # one codebook row = 64 registers
     with pytest.raises(lk.LookatError):
         _run_step(lk, c, 70, 100, 0xAB, functools.partial(lk.lookat_probe_decode_step_entries, 2))
 

@@ -395,6 +395,19 @@ def run_probes(torch, lk, cfg, layers, scale, sink, time_launches, n_launch):
                                                     if wgs else "one round")] = round(vbytes / us / 1e3, 1)
     out["read_stream_GBs_by_launch_shape"] = sweep
     out["read_stream_best_GBs"] = max(sweep.values())
+    # the same bare read in the launch geometries of the decode kernels (contiguous shares, 8 loads in flight per
+    # thread): what those geometries cost before any attention arithmetic
+    BH = cfg.B * cfg.H
+    geoms = [(f"{BH} x 256 threads (lookat_attend_decode: one (b,h) per workgroup)", 256, BH),
+             (f"{BH} x 512 threads (fused step, one (b,h) per workgroup)", 512, BH),
+             (f"{2 * BH} x 256 threads (two shares per (b,h))", 256, 2 * BH),
+             (f"{4 * BH} x 256 threads (four shares per (b,h))", 256, 4 * BH)]
+    if BH % 2 == 0:
+        geoms.insert(2, (f"{BH // 2} x 1024 threads (fused step, two batch entries per workgroup)", 1024, BH // 2))
+    out["read_stream_us_in_kernel_geometries"] = {
+        name: round(loop(lambda i: lk.lookat_probe_stream_read_shaped(layers[i % len(layers)].values, sink, th, 8, wgs, True, True),
+                         n_launch // 4), 2)
+        for name, th, wgs in geoms}
     # attention with the in-kernel ticket merge against the two-launch path, ranges chosen by each
     ws = torch.zeros(max(16, lk.probe_attend_decode_ticket_workspace_bytes(cfg.B, cfg.H, cfg.d_k, cfg.m, cfg.L, 0)),
                      dtype=torch.uint8, device=layers[0].values.device)

@@ -906,12 +906,16 @@ def _capture(fn):
     return graph
 
 
-@pytest.mark.parametrize("g,d_k,m,L,splits", [(4, 128, 8, 3000, 3), (1, 64, 4, 1024, 0), (2, 64, 16, 1537, 2)])
-def test_decode_step_graph_replays_equal_eager(lk, g, d_k, m, L, splits):
-    """The fused step (ranges plus merge kernel where it splits) recorded into a graph: every one of three
+@pytest.mark.parametrize("g,d_k,m,L,splits,B,H", [(4, 128, 8, 3000, 3, 2, 2), (1, 64, 4, 1024, 0, 2, 2), (2, 64, 16, 1537, 2, 2, 2),
+                                                  (1, 64, 4, 800, 0, 22, 12)])
+def test_decode_step_graph_replays_equal_eager(lk, g, d_k, m, L, splits, B, H):
+    """The fused step (ranges plus merge kernel where it splits; in the last case the instance that serves two
+    batch entries per workgroup, which the library takes at 264 (b,h)) recorded into a graph: every one of three
     replays, with eager launches of the same entry point on another context length and synchronisations in
     between, leaves the code cache and the outputs bit-identical to the eager call, which meets the oracle."""
-    B, H, Lmax = 2, 2, L + 29
+    Lmax = L + 29
+    if B * H > 256:
+        assert g == 1 and lk.decode_step_entries_per_workgroup(B, H, d_k, m, L) == 2
     c = _step_case("C3", B, H, Lmax, L, d_k, m, "float16", 9100 + d_k + m + g + L, "recipe", g=g)
     q, k_new, cb, values = dev(c["q"]), dev(c["k_new"]), dev(c["cb"]), dev(c["values"])
     cache = torch.full((B, H, Lmax, m), 0x5A, dtype=torch.uint8, device="cuda")
